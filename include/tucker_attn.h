@@ -1,0 +1,156 @@
+/*
+ * tucker_attn.h -- C ABI of the MI355X (gfx950) Tucker-attention forward library.
+ *
+ * The layer (paper, Definition "Tucker Attention"): the pre-softmax tensor
+ * W = C x1 U1 x2 U2 x3 U3 and the post-softmax tensor W~ = C~ x1 U~1 x2 U~2 x3 U~3
+ * (modes: head, query/output, key/value) define, for a sequence X [N, d],
+ *
+ *     Y[j,k] = sum_i sum_l softmax_l( (X W_i X^T)[j,l] / sqrt(d_head) ) * (W~_i X^T)[k,l]
+ *
+ * (Section "Tensor attention reformulation", the contraction of H1 and H2 over heads
+ * and sequence).  The library evaluates it in the factored order of Sections "KV
+ * Caching", "Rotary Position Embedding" and "Flash Attention": shared latent
+ * Qlat = X U2, K = X U3, V = X U~3; per-head queries Qhat_i = Qlat (C x1 U1)_i; latent
+ * RoPE on Qhat_i and K in the r3-wide key space; online-softmax attention in which one
+ * K/V pair serves all heads; head merge through (C~ x1 U~1)_i; output Y = Z U~2^T.
+ *
+ * Conventions
+ *   - All tensors are row-major and contiguous, last index fastest.
+ *   - "device" pointers are HIP device memory of the GPU that was current at
+ *     tucker_attn_create; "host" pointers are ordinary process memory.
+ *   - The caller owns every buffer it passes (inputs, outputs, caches, workspace); the
+ *     library keeps no pointer after a call returns.  The context owns only host state
+ *     and one device table of rotation cosines/sines allocated in create.
+ *   - forward/decode only enqueue work on the given HIP stream and return; results are
+ *     valid once the caller has synchronised that stream.  Calls that share a
+ *     workspace must be ordered on one stream.
+ *   - Every entry point returns a status (0 = OK, negative = error); nothing aborts,
+ *     throws or prints.  On a non-zero status no kernel has been launched.
+ *   - Readings of the paper where it is silent: softmax scale 1/sqrt(d_head) with d_head a
+ *     free parameter; causal = key n visible to query m iff n <= m; RoPE = rotations of
+ *     adjacent channel pairs (2j,2j+1) by angle position * base^(-2j/r3), applied as
+ *     x'_{2j} = x_{2j} cos - x_{2j+1} sin, x'_{2j+1} = x_{2j} sin + x_{2j+1} cos, to Qhat_i
+ *     (after the core) and to K, never to V; the cache stores rotated K and plain V; a
+ *     decoded token is the last row of the cache.
+ */
+#ifndef TUCKER_ATTN_H
+#define TUCKER_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tucker_attn_ctx tucker_attn_ctx;   /* opaque */
+
+enum { TUCKER_ATTN_F32 = 0, TUCKER_ATTN_BF16 = 1 };
+
+enum {
+  TUCKER_ATTN_OK = 0,
+  TUCKER_ATTN_INVALID_ARG = -1,          /* null pointer, non-positive size, kv_len out of range ... */
+  TUCKER_ATTN_UNSUPPORTED_SHAPE = -2,    /* a shape outside the limits listed at tucker_attn_create  */
+  TUCKER_ATTN_WORKSPACE_TOO_SMALL = -3,
+  TUCKER_ATTN_HIP_ERROR = -4             /* a HIP runtime call failed (allocation, launch)           */
+};
+
+/* Problem description; plain data, copied by create. */
+typedef struct {
+  int32_t d_model;        /* d: width of X and Y                                                   */
+  int32_t n_heads;        /* nH                                                                    */
+  int32_t d_head;         /* enters only as the softmax scale 1/sqrt(d_head)                       */
+  int32_t r1, r2, r3;     /* pre-softmax Tucker ranks: head, query, key                            */
+  int32_t rt1, rt2, rt3;  /* post-softmax Tucker ranks: head, output, value                        */
+  int32_t causal;         /* 0 | 1                                                                 */
+  int32_t use_rope;       /* 0 | 1: latent RoPE over r3 (Definition "Latent RoPE")                 */
+  float   rope_base;      /* e.g. 1e4                                                              */
+  int32_t dtype;          /* TUCKER_ATTN_F32 | TUCKER_ATTN_BF16: storage of X, weights, caches, Y; */
+                          /* products accumulate in fp32 in both cases                             */
+  int32_t max_positions;  /* rotation table covers positions 0 .. max_positions-1 (>= pos0+N, Lmax)*/
+} tucker_attn_config;
+
+/* Device pointers to the weights; read-only, caller-owned. */
+typedef struct {
+  const void *C;    /* [r1, r2, r3]    pre-softmax core                 */
+  const void *U1;   /* [nH, r1]        head-mode basis                  */
+  const void *U2;   /* [d,  r2]        query-mode basis                 */
+  const void *U3;   /* [d,  r3]        key-mode basis                   */
+  const void *Ct;   /* [rt1, rt2, rt3] post-softmax core                */
+  const void *Ut1;  /* [nH, rt1]       head-mode basis (post)           */
+  const void *Ut2;  /* [d,  rt2]       output-mode basis                */
+  const void *Ut3;  /* [d,  rt3]       value-mode basis                 */
+} tucker_attn_weights;
+
+/*
+ * Create a context (Definition "Tucker Attention" fixes the shapes).  Host work plus one
+ * device allocation (rotation table, max_positions * r3/2 cos/sin pairs in fp32, built in
+ * double precision).  Limits of this build, reported as TUCKER_ATTN_UNSUPPORTED_SHAPE:
+ * r3, rt3 <= 128; r2, rt2 <= 512; r1, rt1 <= 64; d_model a multiple of 8; r3 even when
+ * use_rope; ranks need not be multiples of 32 (they are zero-padded internally).
+ */
+int tucker_attn_create(const tucker_attn_config *cfg, tucker_attn_ctx **out);
+
+/* Free the context and its rotation table.  NULL is ignored. */
+void tucker_attn_destroy(tucker_attn_ctx *ctx);
+
+/* Bytes of device workspace tucker_attn_forward needs for a batch of B sequences of N
+ * tokens; 0 if an argument is invalid. */
+size_t tucker_attn_workspace_bytes(const tucker_attn_ctx *ctx, int32_t B, int32_t N);
+
+/* Bytes of device workspace tucker_attn_decode needs for B sequences; 0 if invalid. */
+size_t tucker_attn_decode_workspace_bytes(const tucker_attn_ctx *ctx, int32_t B);
+
+/*
+ * Prefill / training-style forward of B independent sequences of N tokens at positions
+ * pos0 .. pos0+N-1 (the whole path: head-mixed cores, factor projection, latent RoPE,
+ * online-softmax attention, head merge, output projection).
+ *   X            device [B, N, d]      in
+ *   Y            device [B, N, d]      out
+ *   Kcache_out   device [B, Lmax, r3]  out, nullable: rows pos0..pos0+N-1 receive the rotated keys
+ *   Vcache_out   device [B, Lmax, rt3] out, nullable: same rows receive the values
+ *                (both or neither; needs pos0+N <= Lmax)
+ *   workspace    device, >= tucker_attn_workspace_bytes(ctx,B,N) bytes, 256-byte aligned; scratch
+ *   hip_stream   a hipStream_t (NULL = the null stream)
+ */
+int tucker_attn_forward(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
+                        const void *X, void *Y, int32_t B, int32_t N, int32_t pos0,
+                        void *Kcache_out, void *Vcache_out, int32_t Lmax,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One new token per sequence against the latent KV cache (Section "KV Caching").
+ *   x        device [B, d]            in: the new token of each sequence
+ *   y        device [B, d]            out
+ *   Kcache   device [B, Lmax, r3]     in/out: row kv_len[b]-1 is written (rotated key of x[b])
+ *   Vcache   device [B, Lmax, rt3]    in/out: row kv_len[b]-1 is written (value of x[b])
+ *   kv_len   HOST   [B] int32         cache length INCLUDING the new token, 1 <= kv_len[b] <= Lmax;
+ *                                     the query sits at position kv_len[b]-1 and attends rows 0..kv_len[b]-1
+ *   B        1 .. 32
+ * causal in the config is irrelevant here (the query is the last position).
+ */
+int tucker_attn_decode(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
+                       const void *x, void *y, void *Kcache, void *Vcache, int32_t Lmax,
+                       const int32_t *kv_len, int32_t B,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Optional per-kernel timing for benchmarks.  While enabled, forward/decode bracket every
+ * kernel they launch with HIP events recorded on the caller's stream; tucker_attn_profile_read
+ * synchronises those events and returns, for the LAST call, the kernel count and for each
+ * kernel its name and duration.  Event recording perturbs end-to-end time slightly, so
+ * throughput is measured with profiling disabled.
+ *   names   host array of n_max pointers, receives static strings (nullable)
+ *   ms      host array of n_max floats (nullable)
+ * Returns the number of kernels of the last call (<= 16) or a negative status.
+ */
+int tucker_attn_profile_enable(tucker_attn_ctx *ctx, int32_t on);
+int tucker_attn_profile_read(tucker_attn_ctx *ctx, const char **names, float *ms, int32_t n_max);
+
+/* Static, human-readable text for a status code. */
+const char *tucker_attn_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TUCKER_ATTN_H */

@@ -1,0 +1,171 @@
+"""Thin ctypes binding of libtucker_attn.so: argument marshalling only.
+
+Same names as the C ABI (include/tucker_attn.h).  PyTorch supplies device memory and the
+HIP stream; every step of the forward pass runs in the library's kernels.  There is no
+fallback: if the shared library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtucker_attn.so")
+
+TUCKER_ATTN_F32 = 0
+TUCKER_ATTN_BF16 = 1
+
+EXPORTED = [
+    "tucker_attn_create", "tucker_attn_destroy", "tucker_attn_workspace_bytes",
+    "tucker_attn_decode_workspace_bytes", "tucker_attn_forward", "tucker_attn_decode",
+    "tucker_attn_profile_enable", "tucker_attn_profile_read", "tucker_attn_status_string",
+]
+
+
+class TuckerAttnError(RuntimeError):
+    pass
+
+
+class tucker_attn_config(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_head", C.c_int32),
+                ("r1", C.c_int32), ("r2", C.c_int32), ("r3", C.c_int32),
+                ("rt1", C.c_int32), ("rt2", C.c_int32), ("rt3", C.c_int32),
+                ("causal", C.c_int32), ("use_rope", C.c_int32), ("rope_base", C.c_float),
+                ("dtype", C.c_int32), ("max_positions", C.c_int32)]
+
+
+class tucker_attn_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("C", "U1", "U2", "U3", "Ct", "Ut1", "Ut2", "Ut3")]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise TuckerAttnError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2603_30033_amd.build` "
+            "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    ctx_p = C.c_void_p
+    lib.tucker_attn_create.argtypes = [C.POINTER(tucker_attn_config), C.POINTER(ctx_p)]
+    lib.tucker_attn_create.restype = C.c_int
+    lib.tucker_attn_destroy.argtypes = [ctx_p]
+    lib.tucker_attn_destroy.restype = None
+    lib.tucker_attn_workspace_bytes.argtypes = [ctx_p, C.c_int32, C.c_int32]
+    lib.tucker_attn_workspace_bytes.restype = C.c_size_t
+    lib.tucker_attn_decode_workspace_bytes.argtypes = [ctx_p, C.c_int32]
+    lib.tucker_attn_decode_workspace_bytes.restype = C.c_size_t
+    lib.tucker_attn_forward.argtypes = [ctx_p, C.POINTER(tucker_attn_weights), C.c_void_p, C.c_void_p,
+                                        C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                        C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.tucker_attn_forward.restype = C.c_int
+    lib.tucker_attn_decode.argtypes = [ctx_p, C.POINTER(tucker_attn_weights), C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32,
+                                       C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.tucker_attn_decode.restype = C.c_int
+    lib.tucker_attn_profile_enable.argtypes = [ctx_p, C.c_int32]
+    lib.tucker_attn_profile_enable.restype = C.c_int
+    lib.tucker_attn_profile_read.argtypes = [ctx_p, C.POINTER(C.c_char_p), C.POINTER(C.c_float), C.c_int32]
+    lib.tucker_attn_profile_read.restype = C.c_int
+    lib.tucker_attn_status_string.argtypes = [C.c_int]
+    lib.tucker_attn_status_string.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def tucker_attn_status_string(status: int) -> str:
+    return load_library().tucker_attn_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise TuckerAttnError(f"{what}: status {status} ({tucker_attn_status_string(status)})")
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream or None
+
+
+def tucker_attn_create(*, d_model, n_heads, d_head, r1, r2, r3, rt1=None, rt2=None, rt3=None, causal=True,
+                       rope_base=None, dtype="bf16", max_positions=1) -> int:
+    """Returns an opaque context handle (int).  Needs a current HIP device when rope_base is set."""
+    cfg = tucker_attn_config(d_model, n_heads, d_head, r1, r2, r3, rt1 or r1, rt2 or r2, rt3 or r3,
+                             int(bool(causal)), int(rope_base is not None), float(rope_base or 0.0),
+                             {"f32": TUCKER_ATTN_F32, "bf16": TUCKER_ATTN_BF16}[dtype], int(max_positions))
+    ctx = C.c_void_p()
+    _check(load_library().tucker_attn_create(C.byref(cfg), C.byref(ctx)), "tucker_attn_create")
+    return ctx.value
+
+
+def tucker_attn_destroy(ctx: int) -> None:
+    load_library().tucker_attn_destroy(ctx)
+
+
+def tucker_attn_workspace_bytes(ctx: int, B: int, N: int) -> int:
+    return int(load_library().tucker_attn_workspace_bytes(ctx, B, N))
+
+
+def tucker_attn_decode_workspace_bytes(ctx: int, B: int) -> int:
+    return int(load_library().tucker_attn_decode_workspace_bytes(ctx, B))
+
+
+def _weights_struct(w: Dict[str, "object"]) -> tucker_attn_weights:
+    return tucker_attn_weights(*[w[k].data_ptr() for k in ("C", "U1", "U2", "U3", "Ct", "Ut1", "Ut2", "Ut3")])
+
+
+def tucker_attn_forward(ctx: int, weights: Dict, X, Y, pos0: int = 0, Kcache_out=None, Vcache_out=None,
+                        workspace=None, stream=None, check: bool = True) -> int:
+    """X, Y: contiguous device tensors [B, N, d]; weights: dict of contiguous device tensors;
+    workspace: device uint8 tensor of at least tucker_attn_workspace_bytes bytes."""
+    B, N = int(X.shape[0]), int(X.shape[1])
+    Lmax = int(Kcache_out.shape[1]) if Kcache_out is not None else 0
+    ws = _weights_struct(weights)
+    st = load_library().tucker_attn_forward(ctx, C.byref(ws), X.data_ptr(), Y.data_ptr(), B, N, int(pos0),
+                                            _ptr(Kcache_out), _ptr(Vcache_out), Lmax,
+                                            _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                            _stream_ptr(stream))
+    if check:
+        _check(st, "tucker_attn_forward")
+    return st
+
+
+def tucker_attn_decode(ctx: int, weights: Dict, x, y, Kcache, Vcache, kv_len: List[int], workspace=None,
+                       stream=None, check: bool = True) -> int:
+    """x, y: [B, d]; Kcache/Vcache: [B, Lmax, r3]/[B, Lmax, rt3] (updated in place);
+    kv_len: host ints, cache length including the new token."""
+    B = int(x.shape[0])
+    Lmax = int(Kcache.shape[1])
+    lens = (C.c_int32 * B)(*[int(v) for v in kv_len])
+    ws = _weights_struct(weights)
+    st = load_library().tucker_attn_decode(ctx, C.byref(ws), x.data_ptr(), y.data_ptr(), Kcache.data_ptr(),
+                                           Vcache.data_ptr(), Lmax, lens, B,
+                                           _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                           _stream_ptr(stream))
+    if check:
+        _check(st, "tucker_attn_decode")
+    return st
+
+
+def tucker_attn_profile_enable(ctx: int, on: bool) -> None:
+    _check(load_library().tucker_attn_profile_enable(ctx, int(bool(on))), "tucker_attn_profile_enable")
+
+
+def tucker_attn_profile_read(ctx: int) -> List[Tuple[str, float]]:
+    names = (C.c_char_p * 16)()
+    ms = (C.c_float * 16)()
+    n = load_library().tucker_attn_profile_read(ctx, names, ms, 16)
+    if n < 0:
+        _check(n, "tucker_attn_profile_read")
+    return [(names[i].decode(), float(ms[i])) for i in range(n)]

@@ -1,0 +1,439 @@
+// Host side of the C ABI: argument validation, workspace carving and kernel sequencing.
+// Nothing here computes on the CPU except the rotation table built once in create.
+#include "../../include/tucker_attn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.h"
+#include "params.h"
+
+using namespace ta;
+
+namespace {
+constexpr int kMaxKernels = 16;
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+}  // namespace
+
+struct tucker_attn_ctx {
+  tucker_attn_config cfg;
+  int R2, RT2, D, dp;          // padded ranks, common K/V width, padded d
+  int es;                      // bytes per stored element
+  float2* rope;                // device [max_positions][r3/2] or null
+  float qscale;                // log2(e) / sqrt(d_head), folded into the head-mixed core
+  int profile;
+  int n_kernels;
+  const char* names[kMaxKernels];
+  hipEvent_t ev[kMaxKernels + 1];
+  bool ev_created;
+};
+
+namespace {
+
+struct Carver {
+  char* base;
+  size_t off;
+  template <typename P> P* take(size_t bytes) {
+    P* p = reinterpret_cast<P*>(base + off);
+    off += align_up(bytes);
+    return p;
+  }
+};
+
+struct PrefillWs {
+  void *Gt, *Gtil2, *Wcat, *Ut2p, *Qlat, *Kr, *Vt, *O, *Z;
+  size_t bytes;
+};
+struct DecodeWs {
+  void *Gt, *Gtil2, *Wcat, *Ut2p, *Qlat, *Qh, *O, *Z;
+  float *pm, *pl, *po, *part;
+  size_t bytes;
+};
+
+void carve_weights(const tucker_attn_ctx* c, Carver& cv, void*& Gt, void*& Gtil2, void*& Wcat, void*& Ut2p) {
+  const tucker_attn_config& f = c->cfg;
+  Gt = cv.take<char>((size_t)f.n_heads * c->D * c->R2 * c->es);
+  Gtil2 = cv.take<char>((size_t)c->RT2 * f.n_heads * c->D * c->es);
+  Wcat = cv.take<char>((size_t)(c->R2 + 2 * c->D) * c->dp * c->es);
+  Ut2p = cv.take<char>((size_t)c->dp * c->RT2 * c->es);
+}
+
+PrefillWs carve_prefill(const tucker_attn_ctx* c, void* ws, int B, int N) {
+  const tucker_attn_config& f = c->cfg;
+  const size_t Npad = pad64(N), TP = (size_t)B * Npad;
+  Carver cv{static_cast<char*>(ws), 0};
+  PrefillWs w;
+  carve_weights(c, cv, w.Gt, w.Gtil2, w.Wcat, w.Ut2p);
+  w.Qlat = cv.take<char>(TP * c->R2 * c->es);
+  w.Kr = cv.take<char>(TP * c->D * c->es);
+  w.Vt = cv.take<char>((size_t)B * c->D * Npad * c->es);
+  w.O = cv.take<char>(TP * f.n_heads * c->D * c->es);
+  w.Z = cv.take<char>(TP * c->RT2 * c->es);
+  w.bytes = cv.off;
+  return w;
+}
+
+int decode_nsplit(int B) {
+  int n = 512 / B;
+  if (n < 1) n = 1;
+  if (n > 64) n = 64;
+  return n;
+}
+int decode_ksplit(int K) {
+  int nk = (K + 63) / 64;
+  return nk < 16 ? (nk < 1 ? 1 : nk) : 16;
+}
+
+DecodeWs carve_decode(const tucker_attn_ctx* c, void* ws, int B) {
+  const tucker_attn_config& f = c->cfg;
+  const int HB32 = pad32(f.n_heads);
+  const int ns = decode_nsplit(B);
+  Carver cv{static_cast<char*>(ws), 0};
+  DecodeWs w;
+  carve_weights(c, cv, w.Gt, w.Gtil2, w.Wcat, w.Ut2p);
+  w.Qlat = cv.take<char>((size_t)32 * c->R2 * c->es);
+  w.Qh = cv.take<char>((size_t)B * HB32 * c->D * c->es);
+  w.O = cv.take<char>((size_t)B * f.n_heads * c->D * c->es);
+  w.Z = cv.take<char>((size_t)B * c->RT2 * c->es);
+  w.pm = cv.take<float>((size_t)B * ns * HB32 * 4);
+  w.pl = cv.take<float>((size_t)B * ns * HB32 * 4);
+  w.po = cv.take<float>((size_t)B * ns * HB32 * c->D * 4);
+  const size_t p1 = (size_t)decode_ksplit(f.d_model) * B * (c->R2 + 2 * c->D) * 4;
+  const size_t p2 = (size_t)decode_ksplit(f.n_heads * c->D) * B * c->RT2 * 4;
+  w.part = cv.take<float>(p1 > p2 ? p1 : p2);
+  w.bytes = cv.off;
+  return w;
+}
+
+void add_job(PrepArgs& pa, const void* src, const void* coef, void* out, int A, int rows, int cols, int Z,
+             int rows_pad, int cols_pad, long sz, long su, int transposed, int perm, float scale) {
+  PrepJob& j = pa.job[pa.n_jobs++];
+  j.src = src; j.coef = coef; j.out = out;
+  j.A = A; j.rows = rows; j.cols = cols; j.Z = Z;
+  j.rows_pad = rows_pad; j.cols_pad = cols_pad;
+  j.out_stride_z = sz; j.out_stride_u = su;
+  j.transposed = transposed; j.perm = perm; j.scale = scale;
+  j.first_block = pa.total_blocks;
+  pa.total_blocks += Z * (rows_pad / 32) * (cols_pad / 32);
+}
+
+// head-mixed cores and factor matrices in MFMA operand layout; returns the output-factor pointer
+PrepArgs make_prep(const tucker_attn_ctx* c, const tucker_attn_weights* w, void* Gt, void* Gtil2, void* Wcat,
+                   void* Ut2p, const void** ut2_used, long* ut2_ld) {
+  const tucker_attn_config& f = c->cfg;
+  const int es = c->es;
+  PrepArgs pa;
+  std::memset(&pa, 0, sizeof(pa));
+  const long nHD = (long)f.n_heads * c->D;
+  // Gt[i][c][b] = qscale * sum_a U1[i,a] C[a,b,c]
+  add_job(pa, w->C, w->U1, Gt, f.r1, f.r2, f.r3, f.n_heads, c->R2, c->D, (long)c->D * c->R2, c->R2, 1, 1, c->qscale);
+  // Gtil2[b][i*D + c] = sum_a U~1[i,a] C~[a,b,c]
+  add_job(pa, w->Ct, w->Ut1, Gtil2, f.rt1, f.rt2, f.rt3, f.n_heads, c->RT2, c->D, c->D, nHD, 0, 1, 1.f);
+  // Wcat rows: U2^T | U3^T | U~3^T, each [rank_pad][dp]
+  char* wc = static_cast<char*>(Wcat);
+  add_job(pa, w->U2, nullptr, wc, 1, f.d_model, f.r2, 1, c->dp, c->R2, 0, c->dp, 1, 0, 1.f);
+  add_job(pa, w->U3, nullptr, wc + (size_t)c->R2 * c->dp * es, 1, f.d_model, f.r3, 1, c->dp, c->D, 0, c->dp, 1, 0, 1.f);
+  add_job(pa, w->Ut3, nullptr, wc + (size_t)(c->R2 + c->D) * c->dp * es, 1, f.d_model, f.rt3, 1, c->dp, c->D, 0,
+          c->dp, 1, 0, 1.f);
+  if (f.rt2 != c->RT2) {
+    add_job(pa, w->Ut2, nullptr, Ut2p, 1, f.d_model, f.rt2, 1, c->dp, c->RT2, 0, c->RT2, 0, 0, 1.f);
+    *ut2_used = Ut2p;
+  } else {
+    *ut2_used = w->Ut2;
+  }
+  *ut2_ld = c->RT2;
+  return pa;
+}
+
+int pick_tile_n(int m_tiles, long TP) {
+  if ((long)m_tiles * ((TP + 127) / 128) >= 256) return 128;
+  if ((long)m_tiles * ((TP + 63) / 64) >= 256) return 64;
+  return 32;
+}
+
+struct Recorder {
+  tucker_attn_ctx* c;
+  hipStream_t s;
+  bool on;
+  hipError_t begin() {
+    c->n_kernels = 0;
+    if (!on) return hipSuccess;
+    return hipEventRecord(c->ev[0], s);
+  }
+  hipError_t after(const char* name) {
+    if (!on) return hipSuccess;
+    if (c->n_kernels >= kMaxKernels) return hipSuccess;
+    c->names[c->n_kernels] = name;
+    ++c->n_kernels;
+    return hipEventRecord(c->ev[c->n_kernels], s);
+  }
+};
+
+bool weights_ok(const tucker_attn_weights* w) {
+  return w && w->C && w->U1 && w->U2 && w->U3 && w->Ct && w->Ut1 && w->Ut2 && w->Ut3;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tucker_attn_create(const tucker_attn_config* cfg, tucker_attn_ctx** out) {
+  if (!cfg || !out) return TUCKER_ATTN_INVALID_ARG;
+  *out = nullptr;
+  const tucker_attn_config& f = *cfg;
+  if (f.d_model < 1 || f.n_heads < 1 || f.d_head < 1 || f.r1 < 1 || f.r2 < 1 || f.r3 < 1 || f.rt1 < 1 ||
+      f.rt2 < 1 || f.rt3 < 1 || f.max_positions < 1)
+    return TUCKER_ATTN_INVALID_ARG;
+  if (f.dtype != TUCKER_ATTN_F32 && f.dtype != TUCKER_ATTN_BF16) return TUCKER_ATTN_INVALID_ARG;
+  if ((f.causal != 0 && f.causal != 1) || (f.use_rope != 0 && f.use_rope != 1)) return TUCKER_ATTN_INVALID_ARG;
+  if (f.use_rope && !(f.rope_base > 0.f)) return TUCKER_ATTN_INVALID_ARG;
+  if (f.r3 > 128 || f.rt3 > 128 || f.r2 > 512 || f.rt2 > 512 || f.r1 > 64 || f.rt1 > 64)
+    return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  if (f.d_model % 8 != 0) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  if (f.use_rope && (f.r3 % 2) != 0) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  if ((long)f.max_positions * f.r3 > (1l << 31)) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+
+  tucker_attn_ctx* c = new (std::nothrow) tucker_attn_ctx;
+  if (!c) return TUCKER_ATTN_HIP_ERROR;
+  std::memset(c, 0, sizeof(*c));
+  c->cfg = f;
+  c->R2 = pad32(f.r2);
+  c->RT2 = pad32(f.rt2);
+  const int dk = pad32(f.r3), dv = pad32(f.rt3);
+  int D = dk > dv ? dk : dv;
+  if (D == 96) D = 128;
+  c->D = D;
+  c->dp = pad32(f.d_model);
+  c->es = f.dtype == TUCKER_ATTN_F32 ? 4 : 2;
+  c->qscale = (float)(1.4426950408889634 / std::sqrt((double)f.d_head));
+  c->rope = nullptr;
+  if (f.use_rope) {
+    // angle = position * base^(-2j/r3), evaluated in double precision, stored as fp32 (cos, sin)
+    const int half = f.r3 / 2;
+    std::vector<float2> tab((size_t)f.max_positions * half);
+    for (int j = 0; j < half; ++j) {
+      const double theta = std::pow((double)f.rope_base, -2.0 * j / (double)f.r3);
+      for (int p = 0; p < f.max_positions; ++p) {
+        const double a = (double)p * theta;
+        tab[(size_t)p * half + j] = make_float2((float)std::cos(a), (float)std::sin(a));
+      }
+    }
+    if (hipMalloc(&c->rope, tab.size() * sizeof(float2)) != hipSuccess) {
+      delete c;
+      return TUCKER_ATTN_HIP_ERROR;
+    }
+    if (hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice) != hipSuccess) {
+      (void)hipFree(c->rope);
+      delete c;
+      return TUCKER_ATTN_HIP_ERROR;
+    }
+  }
+  *out = c;
+  return TUCKER_ATTN_OK;
+}
+
+void tucker_attn_destroy(tucker_attn_ctx* c) {
+  if (!c) return;
+  if (c->rope) (void)hipFree(c->rope);
+  if (c->ev_created)
+    for (int i = 0; i <= kMaxKernels; ++i) (void)hipEventDestroy(c->ev[i]);
+  delete c;
+}
+
+size_t tucker_attn_workspace_bytes(const tucker_attn_ctx* c, int32_t B, int32_t N) {
+  if (!c || B < 1 || N < 1) return 0;
+  return carve_prefill(c, nullptr, B, N).bytes;
+}
+
+size_t tucker_attn_decode_workspace_bytes(const tucker_attn_ctx* c, int32_t B) {
+  if (!c || B < 1 || B > 32) return 0;
+  return carve_decode(c, nullptr, B).bytes;
+}
+
+int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* X, void* Y, int32_t B,
+                        int32_t N, int32_t pos0, void* Kcache_out, void* Vcache_out, int32_t Lmax, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  if (!c || !weights_ok(w) || !X || !Y || !workspace) return TUCKER_ATTN_INVALID_ARG;
+  if (B < 1 || N < 1 || pos0 < 0) return TUCKER_ATTN_INVALID_ARG;
+  if ((Kcache_out == nullptr) != (Vcache_out == nullptr)) return TUCKER_ATTN_INVALID_ARG;
+  const tucker_attn_config& f = c->cfg;
+  if (Kcache_out && (Lmax < 1 || (long)pos0 + N > Lmax)) return TUCKER_ATTN_INVALID_ARG;
+  if (f.use_rope && (long)pos0 + N > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
+  if ((long)B * pad64(N) > (1l << 30) / 64 || B > 65535) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
+  PrefillWs ws = carve_prefill(c, workspace, B, N);
+  if (workspace_bytes < ws.bytes) return TUCKER_ATTN_WORKSPACE_TOO_SMALL;
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int Npad = pad64(N);
+  const long TP = (long)B * Npad;
+  Recorder rec{c, s, c->profile != 0};
+  if (rec.begin() != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+
+  const void* ut2;
+  long ut2_ld;
+  PrepArgs pa = make_prep(c, w, ws.Gt, ws.Gtil2, ws.Wcat, ws.Ut2p, &ut2, &ut2_ld);
+  if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("prep_weights");
+
+  GemmArgs g;
+  std::memset(&g, 0, sizeof(g));
+  g.A = ws.Wcat; g.lda = c->dp; g.M = c->R2 + 2 * c->D;
+  g.Bsrc = X; g.ldb = f.d_model; g.K = f.d_model;
+  g.Bsz = B; g.N = N; g.Npad = Npad; g.src_padded = 0;
+  g.epi = 0;
+  g.Qlat = ws.Qlat; g.R2 = c->R2; g.Kr = ws.Kr; g.D = c->D; g.Vt = ws.Vt;
+  g.Kcache = Kcache_out; g.Vcache = Vcache_out; g.Lmax = Lmax; g.r3 = f.r3; g.rt3 = f.rt3;
+  g.rope = c->rope; g.pos0 = pos0; g.decode = 0; g.ksplit = 1;
+  if (launch_gemm(f.dtype, g, pick_tile_n((g.M + 127) / 128, TP), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("factor_projection");
+
+  AttnArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.Qlat = ws.Qlat; a.Gt = ws.Gt; a.Kr = ws.Kr; a.Vt = ws.Vt; a.O = ws.O; a.rope = c->rope;
+  a.Bsz = B; a.N = N; a.Npad = Npad; a.nH = f.n_heads; a.R2 = c->R2; a.r3 = f.r3; a.D = c->D;
+  a.causal = f.causal; a.pos0 = pos0;
+  if (launch_attn_prefill(f.dtype, a, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("attention");
+
+  GemmArgs z;
+  std::memset(&z, 0, sizeof(z));
+  z.A = ws.Gtil2; z.lda = (long)f.n_heads * c->D; z.M = c->RT2;
+  z.Bsrc = ws.O; z.ldb = (long)f.n_heads * c->D; z.K = f.n_heads * c->D;
+  z.Bsz = B; z.N = N; z.Npad = Npad; z.src_padded = 1;
+  z.epi = 1; z.Out = ws.Z; z.ldo = c->RT2; z.ksplit = 1; z.R2 = 0; z.D = 0;
+  if (launch_gemm(f.dtype, z, pick_tile_n((z.M + 127) / 128, TP), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("latent_merge");
+
+  GemmArgs y;
+  std::memset(&y, 0, sizeof(y));
+  y.A = ut2; y.lda = ut2_ld; y.M = f.d_model;
+  y.Bsrc = ws.Z; y.ldb = c->RT2; y.K = c->RT2;
+  y.Bsz = B; y.N = N; y.Npad = Npad; y.src_padded = 1;
+  y.epi = 2; y.Out = Y; y.ldo = f.d_model; y.ksplit = 1;
+  if (launch_gemm(f.dtype, y, pick_tile_n((y.M + 127) / 128, TP), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("output_projection");
+  return TUCKER_ATTN_OK;
+}
+
+int tucker_attn_decode(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x, void* y, void* Kcache,
+                       void* Vcache, int32_t Lmax, const int32_t* kv_len, int32_t B, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+  if (!c || !weights_ok(w) || !x || !y || !Kcache || !Vcache || !kv_len || !workspace)
+    return TUCKER_ATTN_INVALID_ARG;
+  if (B < 1 || B > 32 || Lmax < 1) return TUCKER_ATTN_INVALID_ARG;
+  const tucker_attn_config& f = c->cfg;
+  for (int b = 0; b < B; ++b) {
+    if (kv_len[b] < 1 || kv_len[b] > Lmax) return TUCKER_ATTN_INVALID_ARG;
+    if (f.use_rope && kv_len[b] > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
+  }
+  if (f.n_heads > 64) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  if ((f.r3 * c->es) % 16 != 0 || (f.rt3 * c->es) % 16 != 0) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
+  DecodeWs ws = carve_decode(c, workspace, B);
+  if (workspace_bytes < ws.bytes) return TUCKER_ATTN_WORKSPACE_TOO_SMALL;
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  Recorder rec{c, s, c->profile != 0};
+  if (rec.begin() != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+
+  const void* ut2;
+  long ut2_ld;
+  PrepArgs pa = make_prep(c, w, ws.Gt, ws.Gtil2, ws.Wcat, ws.Ut2p, &ut2, &ut2_ld);
+  if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("prep_weights");
+
+  GemmArgs g;
+  std::memset(&g, 0, sizeof(g));
+  g.A = ws.Wcat; g.lda = c->dp; g.M = c->R2 + 2 * c->D;
+  g.Bsrc = x; g.ldb = f.d_model; g.K = f.d_model;
+  g.Bsz = B; g.N = 1; g.Npad = 1; g.src_padded = 0;
+  g.epi = 0;
+  g.Qlat = ws.Qlat; g.R2 = c->R2; g.Kr = nullptr; g.D = c->D; g.Vt = nullptr;
+  g.Kcache = Kcache; g.Vcache = Vcache; g.Lmax = Lmax; g.r3 = f.r3; g.rt3 = f.rt3;
+  g.rope = c->rope; g.pos0 = 0; g.decode = 1;
+  for (int b = 0; b < B; ++b) g.kv_pos[b] = kv_len[b] - 1;
+  g.ksplit = decode_ksplit(g.K); g.part = ws.part;
+  if (launch_gemm(f.dtype, g, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("factor_projection");
+
+  DecodeArgs d;
+  std::memset(&d, 0, sizeof(d));
+  d.Qlat = ws.Qlat; d.Gt = ws.Gt; d.Qh = ws.Qh; d.Kcache = Kcache; d.Vcache = Vcache;
+  d.part_m = ws.pm; d.part_l = ws.pl; d.part_o = ws.po; d.O = ws.O; d.rope = c->rope;
+  d.Bsz = B; d.nH = f.n_heads; d.HB = pad32(f.n_heads) / 32; d.R2 = c->R2; d.r3 = f.r3; d.rt3 = f.rt3;
+  d.D = c->D; d.Lmax = Lmax; d.nsplit = decode_nsplit(B);
+  for (int b = 0; b < B; ++b) d.kv_len[b] = kv_len[b];
+  if (launch_decode_qhat(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("decode_query");
+  if (launch_decode_attn(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("decode_attention");
+  if (launch_decode_merge(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("decode_merge");
+
+  GemmArgs z;
+  std::memset(&z, 0, sizeof(z));
+  z.A = ws.Gtil2; z.lda = (long)f.n_heads * c->D; z.M = c->RT2;
+  z.Bsrc = ws.O; z.ldb = (long)f.n_heads * c->D; z.K = f.n_heads * c->D;
+  z.Bsz = B; z.N = 1; z.Npad = 1; z.src_padded = 1;
+  z.epi = 1; z.Out = ws.Z; z.ldo = c->RT2;
+  z.ksplit = decode_ksplit(z.K); z.part = ws.part;
+  if (launch_gemm(f.dtype, z, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("latent_merge");
+
+  GemmArgs yy;
+  std::memset(&yy, 0, sizeof(yy));
+  yy.A = ut2; yy.lda = ut2_ld; yy.M = f.d_model;
+  yy.Bsrc = ws.Z; yy.ldb = c->RT2; yy.K = c->RT2;
+  yy.Bsz = B; yy.N = 1; yy.Npad = 1; yy.src_padded = 1;
+  yy.epi = 2; yy.Out = y; yy.ldo = f.d_model; yy.ksplit = 1;
+  if (launch_gemm(f.dtype, yy, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("output_projection");
+  return TUCKER_ATTN_OK;
+}
+
+int tucker_attn_profile_enable(tucker_attn_ctx* c, int32_t on) {
+  if (!c) return TUCKER_ATTN_INVALID_ARG;
+  if (on && !c->ev_created) {
+    for (int i = 0; i <= kMaxKernels; ++i)
+      if (hipEventCreate(&c->ev[i]) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    c->ev_created = true;
+  }
+  c->profile = on ? 1 : 0;
+  c->n_kernels = 0;
+  return TUCKER_ATTN_OK;
+}
+
+int tucker_attn_profile_read(tucker_attn_ctx* c, const char** names, float* ms, int32_t n_max) {
+  if (!c || !c->ev_created) return TUCKER_ATTN_INVALID_ARG;
+  const int n = c->n_kernels;
+  if (n == 0) return 0;
+  if (hipEventSynchronize(c->ev[n]) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  for (int i = 0; i < n && i < n_max; ++i) {
+    if (names) names[i] = c->names[i];
+    if (ms) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, c->ev[i], c->ev[i + 1]) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+      ms[i] = t;
+    }
+  }
+  return n;
+}
+
+const char* tucker_attn_status_string(int status) {
+  switch (status) {
+    case TUCKER_ATTN_OK: return "ok";
+    case TUCKER_ATTN_INVALID_ARG: return "invalid argument";
+    case TUCKER_ATTN_UNSUPPORTED_SHAPE: return "unsupported shape";
+    case TUCKER_ATTN_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case TUCKER_ATTN_HIP_ERROR: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

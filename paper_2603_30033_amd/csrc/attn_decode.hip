@@ -1,0 +1,346 @@
+// Decode against the latent KV cache (Section "KV Caching" of the paper): one new query
+// token per sequence attends the cached rotated keys and plain values, width r3, that all
+// heads share.  The heads of a sequence are the MFMA column dimension, so one pass over a
+// cache tile serves every head.
+//
+//   decode_qhat    Qhat_i = qscale * Qlat G_i, latent RoPE at position kv_len-1
+//   decode_attn    split-KV: each workgroup streams a contiguous slice of one sequence's
+//                  cache through LDS once and emits a partial (max, sum, O) per head
+//   decode_merge   log-sum-exp merge of the partials into the normalised O
+#include "common.h"
+#include "params.h"
+
+namespace ta {
+
+// ---------------------------------------------------------------------------------------
+// Qhat^T[c][tok] = sum_b Gt_i[c][b] Qlat[tok][b];  one workgroup per head slot, wave = c-block
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_qhat_kernel(DecodeArgs p) {
+  constexpr int CB = D / 32;
+  const int head = blockIdx.x;                       // 0 .. HB*32-1
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int h = lane / 32, tok = lane % 32;
+  T* Qh = static_cast<T*>(p.Qh);
+  for (int cb = wave; cb < CB; cb += 4) {
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    if (head < p.nH) {
+      const T* Gt = static_cast<const T*>(p.Gt) + (long)head * D * p.R2;
+      const T* Ql = static_cast<const T*>(p.Qlat);
+      for (int bb = 0; bb < p.R2 / 32; ++bb) {
+        Frag<T> xq = tok < p.Bsz ? load_frag<T>(Ql + (long)tok * p.R2 + bb * 32 + 16 * h) : zero_frag<T>();
+        Frag<T> gf = load_frag<T>(Gt + (long)(cb * 32 + tok) * p.R2 + bb * 32 + 16 * h);
+        mma32(acc, gf, xq);
+      }
+      if (p.rope != nullptr && tok < p.Bsz) {
+        const float2* tab = p.rope + (long)(p.kv_len[tok] - 1) * (p.r3 / 2);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; e += 2) {
+            int c = cb * 32 + 8 * q + 4 * h + e;
+            if (c < p.r3) {
+              float2 cs = tab[c / 2];
+              float x0 = acc[4 * q + e], x1 = acc[4 * q + e + 1];
+              acc[4 * q + e] = x0 * cs.x - x1 * cs.y;
+              acc[4 * q + e + 1] = x0 * cs.y + x1 * cs.x;
+            }
+          }
+      }
+    }
+    if (tok < p.Bsz) {
+      T* row = Qh + ((long)tok * p.HB * 32 + head) * D;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        store4(row + cb * 32 + 8 * q + 4 * h, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// split-KV attention over cache rows [first, last) of sequence b
+// ---------------------------------------------------------------------------------------
+template <typename T, int D, int BC> struct DecLds {
+  static constexpr int kRowElems = D + 16 / sizeof(T);
+  static constexpr int kTileElems = BC * kRowElems;
+  static constexpr int kStageElems = 2 * kTileElems;              // K tile, V tile
+  static constexpr size_t kBytes = 2ul * kStageElems * sizeof(T);
+};
+
+__device__ __forceinline__ float lds_elem(const float* p) { return *p; }
+__device__ __forceinline__ bf16 lds_elem(const bf16* p) { return *p; }
+
+template <typename T, int D, int BC, int HB>
+__global__ __launch_bounds__(256) void decode_attn_kernel(DecodeArgs p) {
+  constexpr int CB = D / 32, NB = BC / 32;
+  constexpr int CE = 16 / sizeof(T);
+  constexpr int CPR = D / CE;                                     // 16-byte chunks per tile row
+  constexpr int PT = BC * CPR / 256;                              // chunks per thread per tile
+  static_assert((BC * CPR) % 256 == 0, "tile must fill all threads");
+  using L = DecLds<T, D, BC>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* smem = reinterpret_cast<T*>(smem_raw);
+
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int h = lane / 32, lr = lane % 32;
+  const int b = blockIdx.y, split = blockIdx.x;
+  const int Lb = p.kv_len[b];
+  const int nt_all = (Lb + BC - 1) / BC;
+  const int per = (nt_all + p.nsplit - 1) / p.nsplit;
+  const int t_first = split * per, t_last = min(nt_all, t_first + per);
+  const int HB32 = HB * 32;
+
+  float* pm = p.part_m + ((long)b * p.nsplit + split) * HB32;
+  float* pl = p.part_l + ((long)b * p.nsplit + split) * HB32;
+  float* po = p.part_o + ((long)b * p.nsplit + split) * HB32 * D;
+
+  // query fragments: lane = head, natural order in c
+  Frag<T> qf[HB][CB];
+  {
+    const T* Qh = static_cast<const T*>(p.Qh) + (long)b * HB32 * D;
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) qf[hb][cb] = load_frag<T>(Qh + (long)(hb * 32 + lr) * D + cb * 32 + 16 * h);
+  }
+  const bool has_c = wave < CB;                                   // this wave's value block
+  const int cbw = has_c ? wave : 0;
+  f32x16 oacc[HB];
+  float m_run[HB], l_run[HB];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    m_run[hb] = -INFINITY;
+    l_run[hb] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[hb][e] = 0.f;
+  }
+
+  const T* Kc = static_cast<const T*>(p.Kcache) + (long)b * p.Lmax * p.r3;
+  const T* Vc = static_cast<const T*>(p.Vcache) + (long)b * p.Lmax * p.rt3;
+  u32x4 kreg[PT], vreg[PT];
+  auto g_load = [&](int tile) {
+    const int n0 = tile * BC;
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      int ci = threadIdx.x + i * 256;
+      int row = ci / CPR, col = (ci % CPR) * CE;
+      int n = n0 + row;
+      u32x4 z = {0u, 0u, 0u, 0u};
+      kreg[i] = (n < Lb && col < p.r3) ? *reinterpret_cast<const u32x4*>(Kc + (long)n * p.r3 + col) : z;
+      vreg[i] = (n < Lb && col < p.rt3) ? *reinterpret_cast<const u32x4*>(Vc + (long)n * p.rt3 + col) : z;
+    }
+  };
+  auto s_store = [&](int stage) {
+    T* ks = smem + (long)stage * L::kStageElems;
+    T* vs = ks + L::kTileElems;
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      int ci = threadIdx.x + i * 256;
+      int row = ci / CPR, col = (ci % CPR) * CE;
+      *reinterpret_cast<u32x4*>(ks + row * L::kRowElems + col) = kreg[i];
+      *reinterpret_cast<u32x4*>(vs + row * L::kRowElems + col) = vreg[i];
+    }
+  };
+
+  if (t_first < t_last) {
+    g_load(t_first);
+    s_store(0);
+  }
+  __syncthreads();
+
+  for (int tile = t_first; tile < t_last; ++tile) {
+    const int cur = (tile - t_first) & 1;
+    if (tile + 1 < t_last) g_load(tile + 1);
+    const T* ks = smem + (long)cur * L::kStageElems;
+    const T* vs = ks + L::kTileElems;
+    const int n0 = tile * BC;
+
+    f32x16 s[HB][NB];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[hb][nb][e] = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) {
+        Frag<T> kf = load_frag<T>(ks + (nb * 32 + lr) * L::kRowElems + cb * 32 + 16 * h);
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) mma32(s[hb][nb], kf, qf[hb][cb]);
+      }
+    if (n0 + BC > Lb) {
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            int n = n0 + nb * 32 + 8 * (e / 4) + 4 * h + (e % 4);
+            if (n >= Lb) s[hb][nb][e] = -INFINITY;
+          }
+    }
+    Frag<T> pf[HB][NB];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[hb][nb][e]);
+      mx = halves_max(mx);
+      const float m_new = fmaxf(m_run[hb], mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = fast_exp2(m_run[hb] - m_use);
+      m_run[hb] = m_new;
+      float rs = 0.f;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          float pv = fast_exp2(s[hb][nb][e] - m_use);
+          s[hb][nb][e] = pv;
+          rs += pv;
+        }
+        pf[hb][nb] = to_frag<T>(s[hb][nb]);
+      }
+      l_run[hb] = l_run[hb] * alpha + rs;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[hb][e] *= alpha;
+    }
+    // O^T[c][head] += V^T[c][n] P^T[n][head] for this wave's value block: lane = channel c,
+    // half h gathers keys 8q+4h+r of each 32-key block from the row-major V tile
+    if (has_c) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const T* col = vs + (nb * 32 + 4 * h) * L::kRowElems + cbw * 32 + lr;
+        f32x16 tmp;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) tmp[4 * q + r] = to_f32(lds_elem(col + (8 * q + r) * L::kRowElems));
+        Frag<T> vf = to_frag<T>(tmp);                             // exact: values are already T
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) mma32(oacc[hb], vf, pf[hb][nb]);
+      }
+    }
+    if (tile + 1 < t_last) s_store(cur ^ 1);
+    __syncthreads();
+  }
+
+  // partial results: natural order in c, un-normalised, with running max and sum (base-2 domain)
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    const float l_tot = halves_sum(l_run[hb]);
+    if (wave == 0 && h == 0) {
+      pm[hb * 32 + lr] = m_run[hb];
+      pl[hb * 32 + lr] = l_tot;
+    }
+    if (has_c) {
+      float* row = po + (long)(hb * 32 + lr) * D + cbw * 32;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        store4(row + 8 * q + 4 * h, oacc[hb][4 * q], oacc[hb][4 * q + 1], oacc[hb][4 * q + 2], oacc[hb][4 * q + 3]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// merge of split partials -> O[b][head][c] (c stored in acc order for the latent merge GEMM)
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs p) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  const long total = (long)p.Bsz * p.nH * p.D;
+  if (idx >= total) return;
+  const int c = idx % p.D;
+  const int head = (idx / p.D) % p.nH;
+  const int b = idx / ((long)p.D * p.nH);
+  const int HB32 = p.HB * 32;
+  float mmax = -INFINITY;
+  for (int s = 0; s < p.nsplit; ++s) mmax = fmaxf(mmax, p.part_m[((long)b * p.nsplit + s) * HB32 + head]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < p.nsplit; ++s) {
+    const long ps = ((long)b * p.nsplit + s) * HB32 + head;
+    const float mval = p.part_m[ps];
+    if (mval == -INFINITY) continue;                              // empty split
+    const float w = fast_exp2(mval - mmax);
+    den += w * p.part_l[ps];
+    num += w * p.part_o[ps * p.D + c];
+  }
+  T* O = static_cast<T*>(p.O);
+  store1(O + ((long)b * p.nH + head) * p.D + (c & ~31) + acc_pos(c & 31), num / den);
+}
+
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+static hipError_t qhat_one(const DecodeArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL((decode_qhat_kernel<T, D>), dim3(a.HB * 32), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, hipStream_t s) {
+  if (dtype == 0) {
+    switch (a.D) {
+      case 32: return qhat_one<float, 32>(a, s);
+      case 64: return qhat_one<float, 64>(a, s);
+      case 128: return qhat_one<float, 128>(a, s);
+    }
+  } else {
+    switch (a.D) {
+      case 32: return qhat_one<bf16, 32>(a, s);
+      case 64: return qhat_one<bf16, 64>(a, s);
+      case 128: return qhat_one<bf16, 128>(a, s);
+    }
+  }
+  return hipErrorInvalidValue;
+}
+
+template <typename T, int D, int BC, int HB>
+static hipError_t attn_one(const DecodeArgs& a, hipStream_t s) {
+  size_t smem = DecLds<T, D, BC>::kBytes;
+  auto kern = decode_attn_kernel<T, D, BC, HB>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(a.nsplit, a.Bsz), dim3(256), smem, s, a);
+  return hipGetLastError();
+}
+template <typename T, int BC>
+static hipError_t attn_dispatch(const DecodeArgs& a, hipStream_t s) {
+  if (a.HB == 1) {
+    switch (a.D) {
+      case 32: return attn_one<T, 32, BC, 1>(a, s);
+      case 64: return attn_one<T, 64, BC, 1>(a, s);
+      case 128: return attn_one<T, 128, BC, 1>(a, s);
+    }
+  } else if (a.HB == 2) {
+    switch (a.D) {
+      case 32: return attn_one<T, 32, BC, 2>(a, s);
+      case 64: return attn_one<T, 64, BC, 2>(a, s);
+      case 128: return attn_one<T, 128, BC, 2>(a, s);
+    }
+  }
+  return hipErrorInvalidValue;
+}
+hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s) {
+  return dtype == 0 ? attn_dispatch<float, 32>(a, s) : attn_dispatch<bf16, 64>(a, s);
+}
+
+hipError_t launch_decode_merge(int dtype, const DecodeArgs& a, hipStream_t s) {
+  const long total = (long)a.Bsz * a.nH * a.D;
+  const int blocks = (int)((total + 255) / 256);
+  if (dtype == 0)
+    hipLaunchKernelGGL(decode_merge_kernel<float>, dim3(blocks), dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL(decode_merge_kernel<bf16>, dim3(blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace ta

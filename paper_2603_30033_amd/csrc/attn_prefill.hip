@@ -1,0 +1,310 @@
+// Fused prefill attention for Tucker attention (Sections "Rotary Position Embedding" and
+// "Flash Attention" of the paper): per-head query Qhat_i = Qlat G_i built in a prologue,
+// latent RoPE applied to it in fp32 registers, then online-softmax attention over the ONE
+// latent K/V pair that all heads share, K/V tiles staged once in LDS per workgroup and
+// reused by every head in it.
+//
+// Everything is computed transposed so that an accumulator lane owns one query:
+//   Qhat^T[c][m] = sum_b Gt_i[c][b] Qlat[m][b]         rows c, columns m (queries)
+//   S^T[n][m]    = sum_c K[n][c] Qhat[m][c]            rows n (keys),   columns m
+//   O^T[c][m]   += sum_n V^T[c][n] P^T[n][m]           rows c (values), columns m
+// A lane (column m, half h) then holds 16 keys of a 32-key block in registers, so the row
+// maximum and row sum of the softmax are in-register reductions plus one exchange with the
+// partner lane, and accumulators turn into the next product's operand without any
+// cross-lane movement (see the fragment model in common.h).
+//
+// Workgroup = 4 waves = 4 heads x (32*QB) queries; K/V tile = BC keys, double buffered.
+#include "common.h"
+#include "params.h"
+
+namespace ta {
+
+template <typename T, int D, int BC> struct AttnLds {
+  static constexpr int kKRowElems = D + 16 / sizeof(T);        // K tile rows: D channels + 16 B pad
+  static constexpr int kVRowElems = BC + 16 / sizeof(T);       // V^T tile rows: BC keys + 16 B pad
+  static constexpr int kKElems = BC * kKRowElems;
+  static constexpr int kVElems = D * kVRowElems;
+  static constexpr int kStageElems = kKElems + kVElems;
+  static constexpr size_t kBytes = 2ul * kStageElems * sizeof(T);
+};
+
+template <typename T, int D, int QB, int BC>
+__global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs p) {
+  constexpr int CB = D / 32, NB = BC / 32, TQ = 32 * QB;
+  constexpr int CE = 16 / sizeof(T);                            // elements per 16-byte chunk
+  using L = AttnLds<T, D, BC>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* smem = reinterpret_cast<T*>(smem_raw);
+
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int h = lane / 32, lr = lane % 32;
+  const int n_qtiles = (p.N + TQ - 1) / TQ;
+  const int qt = n_qtiles - 1 - blockIdx.x;                     // heavy (late) query tiles first
+  const int b = blockIdx.z;
+  const int head_raw = blockIdx.y * 4 + wave;
+  const bool head_ok = head_raw < p.nH;
+  const int head = head_ok ? head_raw : p.nH - 1;
+  const int t0 = qt * TQ;
+  const long tok_base = (long)b * p.Npad;
+
+  // ---- prologue: Qhat^T = Gt_i * Qlat^T, RoPE, -> B-operand fragments ---------------------
+  Frag<T> qf[QB][CB];
+  {
+    f32x16 qa[QB][CB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) qa[qb][cb][e] = 0.f;
+    const T* Gt = static_cast<const T*>(p.Gt) + (long)head * D * p.R2;
+    const T* Ql = static_cast<const T*>(p.Qlat);
+    for (int bb = 0; bb < p.R2 / 32; ++bb) {
+      Frag<T> xq[QB];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        int m = t0 + 32 * qb + lr;                              // < Npad because Npad % 64 == 0
+        xq[qb] = load_frag<T>(Ql + (tok_base + m) * p.R2 + bb * 32 + 16 * h);
+      }
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) {
+        Frag<T> gf = load_frag<T>(Gt + (long)(cb * 32 + lr) * p.R2 + bb * 32 + 16 * h);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) mma32(qa[qb][cb], gf, xq[qb]);
+      }
+    }
+    if (p.rope != nullptr) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        int m = t0 + 32 * qb + lr;
+        if (m < p.N) {
+          const float2* tab = p.rope + (long)(p.pos0 + m) * (p.r3 / 2);
+#pragma unroll
+          for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+              for (int e = 0; e < 4; e += 2) {
+                int c = cb * 32 + 8 * q + 4 * h + e;
+                if (c < p.r3) {
+                  float2 cs = tab[c / 2];
+                  float x0 = qa[qb][cb][4 * q + e], x1 = qa[qb][cb][4 * q + e + 1];
+                  qa[qb][cb][4 * q + e] = x0 * cs.x - x1 * cs.y;
+                  qa[qb][cb][4 * q + e + 1] = x0 * cs.y + x1 * cs.x;
+                }
+              }
+        }
+      }
+    }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) qf[qb][cb] = to_frag<T>(qa[qb][cb]);
+  }
+
+  // ---- main loop over key tiles ----------------------------------------------------------
+  f32x16 oacc[QB][CB];
+  float m_run[QB], l_run[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    m_run[qb] = -INFINITY;
+    l_run[qb] = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[qb][cb][e] = 0.f;
+  }
+
+  // keys needed: causal -> 0 .. t0+TQ-1 (clipped to N), else 0 .. N-1
+  const int kv_end = p.causal ? min(p.N, t0 + TQ) : p.N;
+  const int n_tiles = (kv_end + BC - 1) / BC;
+
+  // cooperative staging: K tile = BC rows x D, V^T tile = D rows x BC
+  constexpr int KCH = BC * D / CE, VCH = D * BC / CE;           // 16-byte chunks
+  constexpr int KPT = KCH / 256, VPT = VCH / 256;
+  static_assert(KCH % 256 == 0 && VCH % 256 == 0, "tile must fill all threads");
+  constexpr int KCPR = D / CE, VCPR = BC / CE;                  // chunks per row
+  const T* Kg = static_cast<const T*>(p.Kr) + tok_base * D;
+  const T* Vg = static_cast<const T*>(p.Vt) + (long)b * D * p.Npad;
+  u32x4 kreg[KPT], vreg[VPT];
+  auto g_load = [&](int tile) {
+    const int n0 = tile * BC;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      int ci = threadIdx.x + i * 256;
+      int row = ci / KCPR, cc = ci % KCPR;
+      kreg[i] = *reinterpret_cast<const u32x4*>(Kg + (long)(n0 + row) * D + cc * CE);
+    }
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      int ci = threadIdx.x + i * 256;
+      int row = ci / VCPR, cc = ci % VCPR;
+      vreg[i] = *reinterpret_cast<const u32x4*>(Vg + (long)row * p.Npad + n0 + cc * CE);
+    }
+  };
+  auto s_store = [&](int stage) {
+    T* ks = smem + (long)stage * L::kStageElems;
+    T* vs = ks + L::kKElems;
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      int ci = threadIdx.x + i * 256;
+      int row = ci / KCPR, cc = ci % KCPR;
+      *reinterpret_cast<u32x4*>(ks + row * L::kKRowElems + cc * CE) = kreg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      int ci = threadIdx.x + i * 256;
+      int row = ci / VCPR, cc = ci % VCPR;
+      *reinterpret_cast<u32x4*>(vs + row * L::kVRowElems + cc * CE) = vreg[i];
+    }
+  };
+
+  g_load(0);
+  s_store(0);
+  __syncthreads();
+
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    const int cur = tile & 1;
+    if (tile + 1 < n_tiles) g_load(tile + 1);
+    const T* ks = smem + (long)cur * L::kStageElems;
+    const T* vs = ks + L::kKElems;
+    const int n0 = tile * BC;
+
+    // S^T = K Qhat^T
+    f32x16 s[QB][NB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[qb][nb][e] = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) {
+        Frag<T> kf = load_frag<T>(ks + (nb * 32 + lr) * L::kKRowElems + cb * 32 + 16 * h);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) mma32(s[qb][nb], kf, qf[qb][cb]);
+      }
+
+    // mask: keys beyond the sequence, and (causal) keys after the query
+    const bool need_mask = (n0 + BC > p.N) || (p.causal && n0 + BC - 1 > t0);
+    if (need_mask) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const int m = t0 + 32 * qb + lr;
+        const int lim = p.causal ? min(m, p.N - 1) : p.N - 1;   // last visible key
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            int n = n0 + nb * 32 + 8 * (e / 4) + 4 * h + (e % 4);
+            if (n > lim) s[qb][nb][e] = -INFINITY;
+          }
+      }
+    }
+
+    // online softmax (scores already carry log2(e)/sqrt(d_head))
+    Frag<T> pf[QB][NB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[qb][nb][e]);
+      mx = halves_max(mx);
+      const float m_new = fmaxf(m_run[qb], mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = fast_exp2(m_run[qb] - m_use);
+      m_run[qb] = m_new;
+      float rs = 0.f;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          float pv = fast_exp2(s[qb][nb][e] - m_use);
+          s[qb][nb][e] = pv;
+          rs += pv;
+        }
+        pf[qb][nb] = to_frag<T>(s[qb][nb]);
+      }
+      l_run[qb] = l_run[qb] * alpha + rs;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0ull) {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[qb][cb][e] *= alpha;
+      }
+    }
+
+    // O^T += V^T P^T
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        Frag<T> vf = load_frag<T>(vs + (cb * 32 + lr) * L::kVRowElems + nb * 32 + 16 * h);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) mma32(oacc[qb][cb], vf, pf[qb][nb]);
+      }
+
+    if (tile + 1 < n_tiles) s_store(cur ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: normalise, store O[tok][head][c] (acc order in c) -------------------------
+  if (head_ok) {
+    T* O = static_cast<T*>(p.O);
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const int m = t0 + 32 * qb + lr;
+      const float l_tot = halves_sum(l_run[qb]);
+      const float inv = 1.f / l_tot;
+      if (m < p.N) {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+          f32x16 o = oacc[qb][cb];
+#pragma unroll
+          for (int e = 0; e < 16; ++e) o[e] *= inv;
+          store_frag<T>(O + ((tok_base + m) * p.nH + head) * D + cb * 32 + 16 * h, to_frag<T>(o));
+        }
+      }
+    }
+  }
+}
+
+template <typename T, int D, int QB, int BC>
+static hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
+  constexpr int TQ = 32 * QB;
+  dim3 grid((a.N + TQ - 1) / TQ, (a.nH + 3) / 4, a.Bsz);
+  size_t smem = AttnLds<T, D, BC>::kBytes;
+  auto kern = attn_prefill_kernel<T, D, QB, BC>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_prefill(int dtype, const AttnArgs& a, hipStream_t s) {
+  if (dtype == 0) {
+    switch (a.D) {
+      case 32: return launch_one<float, 32, 1, 32>(a, s);
+      case 64: return launch_one<float, 64, 1, 32>(a, s);
+      case 128: return launch_one<float, 128, 1, 32>(a, s);
+    }
+  } else {
+    switch (a.D) {
+      case 32: return launch_one<bf16, 32, 2, 64>(a, s);
+      case 64: return launch_one<bf16, 64, 2, 64>(a, s);
+      case 128: return launch_one<bf16, 128, 2, 64>(a, s);
+    }
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace ta

@@ -1,0 +1,150 @@
+// Shared device helpers for the gfx950 Tucker-attention kernels: element types, 32x32 MFMA
+// block products on "fragments", LDS/global fragment access.
+//
+// Fragment model.  Every product here is built from 32x32 output blocks with a 32-wide
+// slice of the contraction index.  For such a slice a lane holds 16 elements of an operand:
+// lane l serves operand row (or column) l%32 and the half h = l/32 of the slice.  Which 16
+// of the 32 contraction indices half h holds is free as long as both operands agree:
+//   natural order   half h holds indices 16h .. 16h+15           (both operands from memory)
+//   acc order       half h holds indices 8q+4h+r, q,r in 0..3    (one operand converted in
+//                   registers from an MFMA accumulator, whose lane (column l%32, half h)
+//                   holds rows 8q+4h+r in register 4q+r)
+// Buffers that feed the second kind are stored with each 32-block permuted so that the 16
+// elements of a half are contiguous: index 8q+4h+r sits at position 16h+4q+r.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ta {
+
+typedef __bf16 bf16;
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWave = 64;
+
+__host__ __device__ constexpr int pad32(int x) { return (x + 31) / 32 * 32; }
+__host__ __device__ constexpr int pad64(int x) { return (x + 63) / 64 * 64; }
+
+// position of contraction index x (0..31) inside an acc-ordered 32-block
+__host__ __device__ constexpr int acc_pos(int x) { return 16 * ((x >> 2) & 1) + 4 * (x >> 3) + (x & 3); }
+
+template <typename T> struct Frag;
+template <> struct Frag<float> { f32x4 v[4]; };      // 16 fp32
+template <> struct Frag<bf16> { bf16x8 v[2]; };      // 16 bf16
+
+// acc += A_frag * B_frag over one 32-slice.  Result lane (column = B lane % 32, half h) holds
+// rows 8q+4h+r of the A operand in register 4q+r.
+__device__ __forceinline__ void mma32(f32x16& acc, const Frag<bf16>& a, const Frag<bf16>& b) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v[0], b.v[0], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v[1], b.v[1], acc, 0, 0, 0);
+}
+__device__ __forceinline__ void mma32(f32x16& acc, const Frag<float>& a, const Frag<float>& b) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][j], b.v[i][j], acc, 0, 0, 0);
+}
+
+// accumulator block -> operand fragment (acc order), with rounding to T
+__device__ __forceinline__ Frag<float> to_frag_f32(const f32x16& a) {
+  Frag<float> f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) f.v[i] = f32x4{a[4 * i], a[4 * i + 1], a[4 * i + 2], a[4 * i + 3]};
+  return f;
+}
+__device__ __forceinline__ Frag<bf16> to_frag_bf16(const f32x16& a) {
+  Frag<bf16> f;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      f32x2 two = {a[8 * i + 2 * j], a[8 * i + 2 * j + 1]};
+      bf16x2 pk = __builtin_convertvector(two, bf16x2);
+      f.v[i][2 * j] = pk[0];
+      f.v[i][2 * j + 1] = pk[1];
+    }
+  return f;
+}
+template <typename T> __device__ __forceinline__ Frag<T> to_frag(const f32x16& a);
+template <> __device__ __forceinline__ Frag<float> to_frag<float>(const f32x16& a) { return to_frag_f32(a); }
+template <> __device__ __forceinline__ Frag<bf16> to_frag<bf16>(const f32x16& a) { return to_frag_bf16(a); }
+
+// 16 contiguous elements (32 or 64 bytes, 16-byte aligned) <-> fragment
+template <typename T> __device__ __forceinline__ Frag<T> load_frag(const T* p);
+template <> __device__ __forceinline__ Frag<float> load_frag<float>(const float* p) {
+  Frag<float> f;
+  const f32x4* q = reinterpret_cast<const f32x4*>(p);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) f.v[i] = q[i];
+  return f;
+}
+template <> __device__ __forceinline__ Frag<bf16> load_frag<bf16>(const bf16* p) {
+  Frag<bf16> f;
+  const bf16x8* q = reinterpret_cast<const bf16x8*>(p);
+  f.v[0] = q[0];
+  f.v[1] = q[1];
+  return f;
+}
+template <typename T> __device__ __forceinline__ Frag<T> zero_frag();
+template <> __device__ __forceinline__ Frag<float> zero_frag<float>() {
+  Frag<float> f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) f.v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  return f;
+}
+template <> __device__ __forceinline__ Frag<bf16> zero_frag<bf16>() {
+  Frag<bf16> f;
+  u32x4 z = {0u, 0u, 0u, 0u};
+  f.v[0] = __builtin_bit_cast(bf16x8, z);
+  f.v[1] = f.v[0];
+  return f;
+}
+template <typename T> __device__ __forceinline__ void store_frag(T* p, const Frag<T>& f);
+template <> __device__ __forceinline__ void store_frag<float>(float* p, const Frag<float>& f) {
+  f32x4* q = reinterpret_cast<f32x4*>(p);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) q[i] = f.v[i];
+}
+template <> __device__ __forceinline__ void store_frag<bf16>(bf16* p, const Frag<bf16>& f) {
+  bf16x8* q = reinterpret_cast<bf16x8*>(p);
+  q[0] = f.v[0];
+  q[1] = f.v[1];
+}
+
+// four consecutive accumulator registers (rows 8q+4h .. +3) -> 4 elements of T at p (natural order)
+__device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
+  *reinterpret_cast<f32x4*>(p) = f32x4{a, b, c, d};
+}
+__device__ __forceinline__ void store4(bf16* p, float a, float b, float c, float d) {
+  f32x4 v = {a, b, c, d};
+  *reinterpret_cast<bf16x4*>(p) = __builtin_convertvector(v, bf16x4);
+}
+__device__ __forceinline__ void store1(float* p, float a) { *p = a; }
+__device__ __forceinline__ void store1(bf16* p, float a) { *p = (bf16)a; }
+__device__ __forceinline__ float to_f32(float a) { return a; }
+__device__ __forceinline__ float to_f32(bf16 a) { return (float)a; }
+
+// 16-byte chunk of T elements
+template <typename T> struct Chunk { static constexpr int kElems = 16 / sizeof(T); };
+
+// value held by the partner lane (l ^ 32) combined with ours
+__device__ __forceinline__ float halves_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float halves_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+}  // namespace ta

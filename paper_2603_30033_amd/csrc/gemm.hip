@@ -1,0 +1,330 @@
+// Dense products of the Tucker-attention forward that are plain GEMMs, on bf16/fp32 MFMA:
+//   projection   [Qlat | K | V](tok) = [U2 | U3 | U~3]^T x(tok)      (Qlat = X U2, K = X U3,
+//                V = X U~3 of Section "KV Caching"), with latent RoPE on K in the epilogue
+//                (Definition "Latent RoPE": the key rotation is computed once for all heads)
+//   latent merge Z(tok) = sum_i G~_i O_i(tok)                          (head merge through the
+//                post-softmax core, from the contraction of H1 and H2 over heads)
+//   output       Y(tok) = U~2 Z(tok)                                   (output-mode basis)
+// All three compute acc[m][tok] = sum_k A[m][k] B[tok][k] with the weight side as MFMA rows
+// and tokens as MFMA columns, so that an accumulator lane owns one token and four
+// consecutive output channels per register quad.
+//
+// Tiling: workgroup = 4 waves, tile TM x TN (weights x tokens), contraction staged through
+// LDS in slices of 64 elements, double buffered; LDS rows are padded by 16 bytes so that
+// the 16-byte fragment reads of 8 consecutive rows fall into distinct bank groups.
+#include "common.h"
+#include "params.h"
+
+namespace ta {
+
+constexpr int kKS = 64;   // contraction elements per LDS stage
+
+template <typename T> struct Lds {
+  static constexpr int kRowBytes = kKS * sizeof(T) + 16;
+  static constexpr int kRowElems = kRowBytes / sizeof(T);
+  static constexpr int kChunksPerRow = kKS * sizeof(T) / 16;
+  static constexpr int kChunkElems = 16 / sizeof(T);
+};
+
+// Copy a [ROWS x kKS] slice (rows given by a row-pointer functor, null = zero row) into
+// registers / from registers into LDS.  Each thread moves ROWS*chunks/256 16-byte chunks.
+template <typename T, int ROWS> struct Stager {
+  static constexpr int kChunks = ROWS * Lds<T>::kChunksPerRow;
+  static constexpr int kPerThread = (kChunks + 255) / 256;
+  static_assert(kChunks % 256 == 0, "tile rows must fill all threads");
+  u32x4 r[kPerThread];
+  const T* src[kPerThread];   // chunk address at k = 0, null for a zero row
+  int koff[kPerThread];
+
+  template <class RowPtr>
+  __device__ __forceinline__ void init(RowPtr rowptr) {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      int ci = threadIdx.x + i * 256;
+      int row = ci / Lds<T>::kChunksPerRow, cc = ci % Lds<T>::kChunksPerRow;
+      koff[i] = cc * Lds<T>::kChunkElems;
+      const T* p = rowptr(row);
+      src[i] = p ? p + koff[i] : nullptr;
+    }
+  }
+  __device__ __forceinline__ void load(int k0, int K) {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (src[i] != nullptr && k0 + koff[i] < K) v = *reinterpret_cast<const u32x4*>(src[i] + k0);
+      r[i] = v;
+    }
+  }
+  __device__ __forceinline__ void store(T* lds) const {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      int ci = threadIdx.x + i * 256;
+      int row = ci / Lds<T>::kChunksPerRow, cc = ci % Lds<T>::kChunksPerRow;
+      *reinterpret_cast<u32x4*>(lds + row * Lds<T>::kRowElems + cc * Lds<T>::kChunkElems) = r[i];
+    }
+  }
+};
+
+template <typename T>
+__device__ __forceinline__ float2 rope_cs(const GemmArgs& g, int pos, int pair) {
+  return g.rope[(long)pos * (g.r3 / 2) + pair];
+}
+
+// ---- epilogues: one 32x32 accumulator block = 32 weight rows (m0..) x 32 tokens ----------
+template <typename T>
+__device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, int m0, int tp) {
+  const int lane = threadIdx.x % kWave;
+  const int h = lane / 32;
+  const int TP = g.Bsz * g.Npad;
+  if (tp >= TP) return;
+  const int b = tp / g.Npad, n = tp % g.Npad;
+  const bool valid = n < g.N;
+
+  if (g.epi == 0) {
+    const int pos = g.decode ? g.kv_pos[b] : g.pos0 + n;
+    if (m0 < g.R2) {                                            // ---- Qlat, acc order
+      T* dst = static_cast<T*>(g.Qlat) + (long)tp * g.R2 + m0 + 16 * h;
+      store_frag<T>(dst, to_frag<T>(acc));
+    } else if (m0 < g.R2 + g.D) {                               // ---- K, rotated
+      const int c0 = m0 - g.R2;
+      if (g.rope != nullptr && valid) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; e += 2) {
+            int c = c0 + 8 * q + 4 * h + e;
+            if (c < g.r3) {
+              float2 cs = rope_cs<T>(g, pos, c / 2);
+              float x0 = acc[4 * q + e], x1 = acc[4 * q + e + 1];
+              acc[4 * q + e] = x0 * cs.x - x1 * cs.y;
+              acc[4 * q + e + 1] = x0 * cs.y + x1 * cs.x;
+            }
+          }
+      }
+      if (g.Kr != nullptr) {
+        T* dst = static_cast<T*>(g.Kr) + (long)tp * g.D + c0 + 16 * h;
+        store_frag<T>(dst, to_frag<T>(acc));
+      }
+      if (g.Kcache != nullptr && valid) {
+        T* row = static_cast<T*>(g.Kcache) + ((long)b * g.Lmax + pos) * g.r3;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          int c = c0 + 8 * q + 4 * h;
+          if (c + 3 < g.r3 && (g.r3 % 4) == 0)
+            store4(row + c, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+          else
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (c + e < g.r3) store1(row + c + e, acc[4 * q + e]);
+        }
+      }
+    } else {                                                    // ---- V
+      const int c0 = m0 - g.R2 - g.D;
+      if (g.Vt != nullptr) {
+        // Vt[b][c][n], n stored at its acc-order position inside its 32-block
+        T* base = static_cast<T*>(g.Vt) + (long)b * g.D * g.Npad + (n & ~31) + acc_pos(n & 31);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            int c = c0 + 8 * q + 4 * h + e;
+            store1(base + (long)c * g.Npad, acc[4 * q + e]);
+          }
+      }
+      if (g.Vcache != nullptr && valid) {
+        T* row = static_cast<T*>(g.Vcache) + ((long)b * g.Lmax + pos) * g.rt3;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          int c = c0 + 8 * q + 4 * h;
+          if (c + 3 < g.rt3 && (g.rt3 % 4) == 0)
+            store4(row + c, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+          else
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (c + e < g.rt3) store1(row + c + e, acc[4 * q + e]);
+        }
+      }
+    }
+  } else if (g.epi == 1) {                                      // ---- Z, natural order, padded tokens
+    T* row = static_cast<T*>(g.Out) + (long)tp * g.ldo;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      int c = m0 + 8 * q + 4 * h;
+      if (c < g.M) store4(row + c, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    }
+  } else {                                                      // ---- Y, caller's [B][N][d]
+    if (!valid) return;
+    T* row = static_cast<T*>(g.Out) + ((long)b * g.N + n) * g.ldo;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      int c = m0 + 8 * q + 4 * h;
+      if (c + 3 < g.M)
+        store4(row + c, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+      else
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (c + e < g.M) store1(row + c + e, acc[4 * q + e]);
+    }
+  }
+}
+
+// TM x TN tile, WGM x WGN waves
+template <typename T, int TM, int TN, int WGM, int WGN>
+__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
+  static_assert(WGM * WGN == 4, "four waves");
+  constexpr int MB = TM / WGM / 32, NB = TN / WGN / 32;
+  constexpr int RE = Lds<T>::kRowElems;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* smem = reinterpret_cast<T*>(smem_raw);
+  // stage s: A rows [TM], then B rows [TN]
+  auto stageA = [&](int s) { return smem + (long)s * (TM + TN) * RE; };
+  auto stageB = [&](int s) { return smem + (long)s * (TM + TN) * RE + TM * RE; };
+
+  const int m_tile = blockIdx.x * TM, t_tile = blockIdx.y * TN;
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int wm = wave % WGM, wn = wave / WGM;
+  const int h = lane / 32, lr = lane % 32;
+  const int TP = g.Bsz * g.Npad;
+
+  const T* A = static_cast<const T*>(g.A);
+  const T* Bs = static_cast<const T*>(g.Bsrc);
+  auto rowA = [&](int r) -> const T* {
+    int m = m_tile + r;
+    return m < g.M ? A + (long)m * g.lda : nullptr;
+  };
+  auto rowB = [&](int r) -> const T* {
+    int tp = t_tile + r;
+    if (tp >= TP) return nullptr;
+    if (g.src_padded) return Bs + (long)tp * g.ldb;
+    int b = tp / g.Npad, n = tp % g.Npad;
+    return n < g.N ? Bs + ((long)b * g.N + n) * g.ldb : nullptr;
+  };
+
+  f32x16 acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  Stager<T, TM> sa;
+  Stager<T, TN> sb;
+  const int nk_all = (g.K + kKS - 1) / kKS;
+  const int per = (nk_all + g.ksplit - 1) / g.ksplit;
+  const int ks0 = blockIdx.z * per;
+  const int nk = min(nk_all, ks0 + per);
+  sa.init(rowA);
+  sb.init(rowB);
+  sa.load(ks0 * kKS, g.K);
+  sb.load(ks0 * kKS, g.K);
+  sa.store(stageA(0));
+  sb.store(stageB(0));
+  __syncthreads();
+
+  for (int ks = ks0; ks < nk; ++ks) {
+    const int cur = (ks - ks0) & 1;
+    if (ks + 1 < nk) {
+      sa.load((ks + 1) * kKS, g.K);
+      sb.load((ks + 1) * kKS, g.K);
+    }
+    const T* la = stageA(cur) + (wm * MB * 32 + lr) * RE + 16 * h;
+    const T* lb = stageB(cur) + (wn * NB * 32 + lr) * RE + 16 * h;
+#pragma unroll
+    for (int kb = 0; kb < kKS / 32; ++kb) {
+      Frag<T> fa[MB], fb[NB];
+#pragma unroll
+      for (int i = 0; i < MB; ++i) fa[i] = load_frag<T>(la + i * 32 * RE + kb * 32);
+#pragma unroll
+      for (int j = 0; j < NB; ++j) fb[j] = load_frag<T>(lb + j * 32 * RE + kb * 32);
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) mma32(acc[i][j], fa[i], fb[j]);
+    }
+    if (ks + 1 < nk) {
+      sa.store(stageA(cur ^ 1));
+      sb.store(stageB(cur ^ 1));
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      int m0 = m_tile + (wm * MB + i) * 32;
+      int tp = t_tile + (wn * NB + j) * 32 + lr;
+      const int Mp = (g.epi == 0) ? g.R2 + 2 * g.D : pad32(g.M);
+      if (m0 >= Mp) continue;
+      if (g.ksplit > 1) {
+        if (tp < TP) {
+          float* dst = g.part + ((long)blockIdx.z * TP + tp) * Mp + m0 + 4 * h;
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            store4(dst + 8 * q, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        }
+      } else {
+        epilogue_block<T>(g, acc[i][j], m0, tp);
+      }
+    }
+}
+
+// sum of split-K partial tiles, then the ordinary epilogue; one wave per 32x32 block
+template <typename T>
+__global__ __launch_bounds__(64) void splitk_reduce_kernel(GemmArgs g) {
+  const int lane = threadIdx.x, h = lane / 32, lr = lane % 32;
+  const int TP = g.Bsz * g.Npad;
+  const int Mp = (g.epi == 0) ? g.R2 + 2 * g.D : pad32(g.M);
+  const int m0 = blockIdx.x * 32, tp = blockIdx.y * 32 + lr;
+  f32x16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  if (tp < TP) {
+    for (int z = 0; z < g.ksplit; ++z) {
+      const float* src = g.part + ((long)z * TP + tp) * Mp + m0 + 4 * h;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        f32x4 v = *reinterpret_cast<const f32x4*>(src + 8 * q);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[4 * q + r] += v[r];
+      }
+    }
+  }
+  epilogue_block<T>(g, acc, m0, tp);
+}
+
+template <typename T, int TM, int TN, int WGM, int WGN>
+static hipError_t launch_one(const GemmArgs& a, int m_rows, hipStream_t s) {
+  const int TP = a.Bsz * a.Npad;
+  dim3 grid((m_rows + TM - 1) / TM, (TP + TN - 1) / TN, a.ksplit > 1 ? a.ksplit : 1);
+  size_t smem = 2ul * (TM + TN) * Lds<T>::kRowBytes;
+  auto kern = gemm_kernel<T, TM, TN, WGM, WGN>;
+  static bool attr_done = false;   // raise the dynamic LDS limit once per instantiation
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || a.ksplit <= 1) return e;
+  dim3 rgrid((m_rows + 31) / 32, (TP + 31) / 32);
+  hipLaunchKernelGGL(splitk_reduce_kernel<T>, rgrid, dim3(64), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm(int dtype, const GemmArgs& a, int tile_n, hipStream_t s) {
+  const int m_rows = (a.epi == 0) ? a.R2 + 2 * a.D : a.M;
+  if (dtype == 0) {
+    if (tile_n >= 128) return launch_one<float, 128, 128, 2, 2>(a, m_rows, s);
+    if (tile_n >= 64) return launch_one<float, 128, 64, 2, 2>(a, m_rows, s);
+    return launch_one<float, 128, 32, 4, 1>(a, m_rows, s);
+  }
+  if (tile_n >= 128) return launch_one<bf16, 128, 128, 2, 2>(a, m_rows, s);
+  if (tile_n >= 64) return launch_one<bf16, 128, 64, 2, 2>(a, m_rows, s);
+  return launch_one<bf16, 128, 32, 4, 1>(a, m_rows, s);
+}
+
+}  // namespace ta

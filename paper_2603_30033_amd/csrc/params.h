@@ -1,0 +1,101 @@
+// Kernel argument structures and launcher declarations shared by the host API and the
+// device code.  All pointers are device pointers; all sizes are in elements unless a name
+// says bytes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ta {
+
+// ---- weight preparation (head-mixed cores, transposed factor matrices) ------------------
+// out[z][u][v] = scale * sum_a coef[z][a] * src[a][row][col]   with (u,v) = (col,row) when
+// transposed, (row,col) otherwise; rows/cols beyond the source extents read as zero so the
+// padded part of the output is written as zero.  perm: store column v of each 32-block at
+// its acc-order position.
+struct PrepJob {
+  const void* src;      // [A][rows][cols]
+  const void* coef;     // [Z][A] or null (A must be 1, coefficient 1)
+  void* out;
+  int A, rows, cols;    // source extents
+  int Z;
+  int rows_pad, cols_pad;   // padded extents covered by tiles (multiples of 32)
+  long out_stride_z, out_stride_u;
+  int transposed, perm;
+  float scale;
+  int first_block;      // prefix sum of tile counts
+};
+constexpr int kMaxPrepJobs = 8;
+struct PrepArgs {
+  PrepJob job[kMaxPrepJobs];
+  int n_jobs;
+  int total_blocks;
+};
+
+// ---- generic product  acc[m][tok] = sum_k A[m][k] * Btok[tok][k]  with three epilogues ---
+struct GemmArgs {
+  const void* A;        // [M][lda] weights side (rows beyond M read as zero)
+  long lda;
+  int M;
+  const void* Bsrc;     // token side
+  long ldb;
+  int K;                // contraction length (elements beyond K read as zero)
+  // token indexing: padded token tp = b*Npad + n ; source row exists iff n < N
+  int Bsz, N, Npad;
+  int src_padded;       // 1: Bsrc rows are indexed by tp; 0: by b*N+n (caller's X)
+  // epilogue outputs
+  int epi;              // 0 = projection, 1 = latent merge Z, 2 = output Y
+  // projection
+  void* Qlat; int R2;           // [TP][R2] acc order
+  void* Kr;   int D;            // [TP][D]  acc order, rotated
+  void* Vt;                     // [B][D][Npad], n in acc order within 32-blocks; null in decode
+  void* Kcache; void* Vcache;   // nullable [B][Lmax][r3]/[B][Lmax][rt3], natural order
+  int Lmax, r3, rt3;
+  const float2* rope;           // [max_pos][r3/2] (cos, sin) or null
+  int pos0;
+  int decode;                   // 1: one token per sequence, position/cache row from kv_pos[b]
+  int kv_pos[32];
+  // Z / Y
+  void* Out; long ldo;          // Z: [TP][ldo] natural order;  Y: [B][N][ldo] natural order
+  // split-K (decode-sized token counts): ksplit > 1 writes fp32 partial tiles to part
+  // [ksplit][TP][Mp] (Mp = weight rows padded to 32); a second kernel sums them and runs the
+  // epilogue
+  int ksplit;
+  float* part;
+};
+
+// ---- prefill attention ---------------------------------------------------------------------
+struct AttnArgs {
+  const void* Qlat;   // [TP][R2] acc order
+  const void* Gt;     // [nH][D][R2]  Gt[i][c][b] = qscale * G_i[b][c], b in acc order
+  const void* Kr;     // [TP][D]
+  const void* Vt;     // [B][D][Npad]
+  void* O;            // [TP][nH][D] acc order in c, normalised
+  const float2* rope; // or null
+  int Bsz, N, Npad, nH, R2, r3, D;   // D = padded common width of K and V (32, 64 or 128)
+  int causal, pos0;
+};
+
+// ---- decode ------------------------------------------------------------------------------
+struct DecodeArgs {
+  const void* Qlat;    // [32][R2] acc order (rows >= B are zero)
+  const void* Gt;      // as above
+  void* Qh;            // [B][HB*32][D] natural order, rotated, scaled (rows >= nH zero)
+  const void* Kcache;  // [B][Lmax][r3]
+  const void* Vcache;  // [B][Lmax][rt3]
+  float* part_m;       // [B][nsplit][HB*32]
+  float* part_l;
+  float* part_o;       // [B][nsplit][HB*32][D]
+  void* O;             // [32][nH][D] acc order in c (rows >= B zero)
+  const float2* rope;
+  int Bsz, nH, HB, R2, r3, rt3, D, Lmax, nsplit;
+  int kv_len[32];
+};
+
+hipError_t launch_prep(int dtype, const PrepArgs& a, hipStream_t s);
+hipError_t launch_gemm(int dtype, const GemmArgs& a, int tile_n, hipStream_t s);
+hipError_t launch_attn_prefill(int dtype, const AttnArgs& a, hipStream_t s);
+hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, hipStream_t s);
+hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s);
+hipError_t launch_decode_merge(int dtype, const DecodeArgs& a, hipStream_t s);
+
+}  // namespace ta

@@ -1,0 +1,66 @@
+// Weight preparation: the head-mixed cores G_i = sum_a U1[i,a] C[a] (the "x1 U1" of the
+// paper's per-head query Qhat = C x1 U1 x2 (X U2)) and G~_i for the post-softmax tensor, and
+// transposed / zero-padded copies of the factor matrices, in the operand layouts the MFMA
+// kernels read.  One launch; every 32x32 tile of every output is one workgroup.
+#include "common.h"
+#include "params.h"
+
+namespace ta {
+
+template <typename T>
+__global__ __launch_bounds__(256) void prep_kernel(PrepArgs args) {
+  __shared__ float tile[32][33];
+  int blk = blockIdx.x;
+  int ji = 0;
+#pragma unroll
+  for (int j = 1; j < kMaxPrepJobs; ++j)
+    if (j < args.n_jobs && blk >= args.job[j].first_block) ji = j;
+  const PrepJob& jb = args.job[ji];
+  int local = blk - jb.first_block;
+  int tiles_r = jb.rows_pad / 32, tiles_c = jb.cols_pad / 32;
+  int z = local / (tiles_r * tiles_c);
+  int rem = local % (tiles_r * tiles_c);
+  int r0 = (rem / tiles_c) * 32, c0 = (rem % tiles_c) * 32;
+  int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
+  const T* src = static_cast<const T*>(jb.src);
+  const T* coef = static_cast<const T*>(jb.coef);
+  T* out = static_cast<T*>(jb.out);
+
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    int row = r0 + ty + 8 * rr, col = c0 + tx;
+    float acc = 0.f;
+    if (row < jb.rows && col < jb.cols) {
+      for (int a = 0; a < jb.A; ++a) {
+        float cf = coef ? to_f32(coef[(long)z * jb.A + a]) : 1.f;
+        acc += cf * to_f32(src[((long)a * jb.rows + row) * jb.cols + col]);
+      }
+    }
+    tile[ty + 8 * rr][tx] = acc * jb.scale;
+  }
+  __syncthreads();
+  int vpos = jb.perm ? acc_pos(tx) : tx;
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    int a = ty + 8 * rr;
+    long u, v;
+    float val;
+    if (jb.transposed) {
+      u = c0 + a; v = r0 + vpos; val = tile[tx][a];
+    } else {
+      u = r0 + a; v = c0 + vpos; val = tile[a][tx];
+    }
+    store1(out + (long)z * jb.out_stride_z + u * jb.out_stride_u + v, val);
+  }
+}
+
+hipError_t launch_prep(int dtype, const PrepArgs& a, hipStream_t s) {
+  if (a.total_blocks <= 0) return hipSuccess;
+  if (dtype == 0)
+    hipLaunchKernelGGL(prep_kernel<float>, dim3(a.total_blocks), dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL(prep_kernel<bf16>, dim3(a.total_blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace ta

@@ -1,0 +1,74 @@
+"""Helpers for callers of the binding (tests, smoke, bench): move a generated workload to
+the device and drive the C-ABI library through the ctypes binding.  No arithmetic of the
+method lives here."""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from paper_2603_30033_amd import binding as ta
+from paper_2603_30033_amd import workloads as wl
+
+W_KEYS = ("C", "U1", "U2", "U3", "Ct", "Ut1", "Ut2", "Ut3")
+
+
+def torch_dtype(dtype: str):
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+
+
+def to_device(a: np.ndarray, dtype: str) -> torch.Tensor:
+    """Host fp32 array (already rounded to the storage type) -> contiguous device tensor."""
+    return torch.from_numpy(np.ascontiguousarray(a)).to(torch_dtype(dtype)).cuda().contiguous()
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+class Layer:
+    """A context plus device copies of one workload's weights."""
+
+    def __init__(self, w: wl.Workload, inp: Dict[str, np.ndarray], max_positions: Optional[int] = None):
+        self.w = w
+        rt1, rt2, rt3 = w.ranks_post()
+        if max_positions is None:
+            max_positions = max(w.pos0 + w.N, w.kv_len, 1)
+        self.ctx = ta.tucker_attn_create(
+            d_model=w.d_model, n_heads=w.n_heads, d_head=w.d_head, r1=w.r1, r2=w.r2, r3=w.r3,
+            rt1=rt1, rt2=rt2, rt3=rt3, causal=w.causal, rope_base=w.rope_base, dtype=w.dtype,
+            max_positions=max_positions)
+        self.weights = {k: to_device(inp[k], w.dtype) for k in W_KEYS}
+        self._ws = None
+
+    def close(self):
+        if self.ctx is not None:
+            ta.tucker_attn_destroy(self.ctx)
+            self.ctx = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def workspace(self, nbytes: int) -> torch.Tensor:
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        return self._ws
+
+    def forward(self, X: torch.Tensor, pos0: int = 0, Kc=None, Vc=None, Y=None) -> torch.Tensor:
+        B, N = X.shape[0], X.shape[1]
+        if Y is None:
+            Y = torch.empty_like(X)
+        ws = self.workspace(ta.tucker_attn_workspace_bytes(self.ctx, B, N))
+        ta.tucker_attn_forward(self.ctx, self.weights, X, Y, pos0, Kc, Vc, ws)
+        return Y
+
+    def decode(self, x: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, kv_len, y=None) -> torch.Tensor:
+        if y is None:
+            y = torch.empty_like(x)
+        ws = self.workspace(ta.tucker_attn_decode_workspace_bytes(self.ctx, x.shape[0]))
+        ta.tucker_attn_decode(self.ctx, self.weights, x, y, Kc, Vc, [int(v) for v in kv_len], ws)
+        return y

@@ -1,0 +1,81 @@
+"""The C-ABI library loads and exports every symbol the header declares; host-side argument
+checks that need no GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2603_30033_amd import binding as ta
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "tucker_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tucker_attn_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ta.load_library()
+    names = header_functions()
+    assert sorted(ta.EXPORTED) == names
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    assert ta.tucker_attn_status_string(0) == "ok"
+    for s in (-1, -2, -3, -4):
+        assert ta.tucker_attn_status_string(s) not in ("ok", "unknown status")
+    assert ta.tucker_attn_status_string(-99) == "unknown status"
+
+
+def _cfg(**kw):
+    base = dict(d_model=256, n_heads=4, d_head=64, r1=2, r2=32, r3=32, causal=True, rope_base=None,
+                dtype="f32", max_positions=128)
+    base.update(kw)
+    return base
+
+
+def test_create_rejects_bad_configs_without_touching_the_gpu():
+    lib = ta.load_library()
+    assert lib.tucker_attn_create(None, None) == -1
+    for bad, status in [(dict(d_model=0), -1), (dict(r3=0), -1), (dict(r3=160), -2), (dict(r2=1024), -2),
+                        (dict(d_model=100), -2), (dict(n_heads=0), -1)]:
+        with pytest.raises(ta.TuckerAttnError) as e:
+            ta.tucker_attn_create(**_cfg(**bad))
+        assert f"status {status} " in str(e.value)
+    cfg = ta.tucker_attn_config(256, 4, 64, 2, 32, 31, 2, 32, 32, 1, 1, 1e4, 0, 128)   # odd r3 with RoPE
+    ctx = C.c_void_p()
+    assert lib.tucker_attn_create(C.byref(cfg), C.byref(ctx)) == -2
+
+
+def test_workspace_sizes_and_host_side_argument_checks():
+    ctx = ta.tucker_attn_create(**_cfg())          # no RoPE table -> no device allocation
+    try:
+        assert ta.tucker_attn_workspace_bytes(ctx, 0, 16) == 0
+        assert ta.tucker_attn_workspace_bytes(ctx, 1, 0) == 0
+        small, big = ta.tucker_attn_workspace_bytes(ctx, 1, 64), ta.tucker_attn_workspace_bytes(ctx, 2, 128)
+        assert 0 < small < big and small % 256 == 0
+        assert ta.tucker_attn_workspace_bytes(ctx, 1, 1) == small          # tokens are padded to 64
+        assert ta.tucker_attn_decode_workspace_bytes(ctx, 33) == 0
+        assert ta.tucker_attn_decode_workspace_bytes(ctx, 4) > 0
+        lib = ta.load_library()
+        w = ta.tucker_attn_weights(*([1] * 8))
+        # null X / Y / workspace, bad sizes: rejected on the host before any launch
+        assert lib.tucker_attn_forward(ctx, C.byref(w), None, None, 1, 16, 0, None, None, 0, None, 0, None) == -1
+        assert lib.tucker_attn_forward(ctx, C.byref(w), 256, 256, 0, 16, 0, None, None, 0, 256, 1 << 30, None) == -1
+        assert lib.tucker_attn_forward(ctx, C.byref(w), 256, 256, 1, 16, -1, None, None, 0, 256, 1 << 30, None) == -1
+        assert lib.tucker_attn_forward(ctx, C.byref(w), 256, 256, 1, 16, 0, 256, None, 64, 256, 1 << 30, None) == -1
+        assert lib.tucker_attn_forward(ctx, C.byref(w), 256, 256, 1, 16, 0, None, None, 0, 256, 16, None) == -3
+        assert lib.tucker_attn_forward(ctx, C.byref(w), 256, 256, 1, 16, 0, None, None, 0, 257, 1 << 30, None) == -1
+        lens = (C.c_int32 * 2)(5, 0)
+        assert lib.tucker_attn_decode(ctx, C.byref(w), 256, 256, 256, 256, 8, lens, 2, 256, 1 << 30, None) == -1
+        lens = (C.c_int32 * 2)(5, 9)
+        assert lib.tucker_attn_decode(ctx, C.byref(w), 256, 256, 256, 256, 8, lens, 2, 256, 1 << 30, None) == -1
+        lens = (C.c_int32 * 2)(5, 8)
+        assert lib.tucker_attn_decode(ctx, C.byref(w), 256, 256, 256, 256, 8, lens, 2, 256, 16, None) == -3
+    finally:
+        ta.tucker_attn_destroy(ctx)

@@ -1,0 +1,220 @@
+"""GPU parity: the HIP library, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Tolerances (relative L2 over the compared outputs): 1e-5 for fp32 storage,
+2e-2 for bf16 storage."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tucker_oracle as orc
+from paper_2603_30033_amd import binding as ta
+from paper_2603_30033_amd import workloads as wl
+from paper_2603_30033_amd.device import Layer, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def oracle_forward(w, inp, rows=None, batches=None, pos0=None):
+    return orc.per_head_forward(inp["X"], wl.weights_of(inp), w.d_head, w.causal, w.rope_base,
+                                pos0=w.pos0 if pos0 is None else pos0, rows=rows, batches=batches)
+
+
+def run_forward(w, inp, pos0=None, with_cache=False, Lmax=None):
+    with Layer(w, inp, max_positions=(w.pos0 if pos0 is None else pos0) + w.N + 8) as layer:
+        X = to_device(inp["X"], w.dtype)
+        Kc = Vc = None
+        if with_cache:
+            rt3 = w.ranks_post()[2]
+            Kc = torch.zeros((w.B, Lmax, w.r3), dtype=X.dtype, device="cuda")
+            Vc = torch.zeros((w.B, Lmax, rt3), dtype=X.dtype, device="cuda")
+        Y = layer.forward(X, pos0=w.pos0 if pos0 is None else pos0, Kc=Kc, Vc=Vc)
+        torch.cuda.synchronize()
+        out = to_host(Y)
+        if with_cache:
+            return out, to_host(Kc), to_host(Vc)
+        return out
+
+
+def check(y_gpu, y_ref, dtype, what=""):
+    assert np.all(np.isfinite(y_gpu)), what
+    err = orc.relative_l2(y_gpu, y_ref)
+    assert err <= TOL[dtype], f"{what}: relative L2 {err:.3e} > {TOL[dtype]:.0e}"
+    return err
+
+
+# ---- the five named workloads --------------------------------------------------------------------
+
+def test_config1_tiny_f32_full():
+    w = wl.WORKLOADS["tiny_f32"]
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), w.dtype, w.name)
+
+
+def test_config2_gpt2_small_scaled_full_and_full_size_sampled():
+    base = wl.WORKLOADS["gpt2_small"]
+    w = wl.scaled(base, B=2, N=333)                       # several tiles and a ragged tail, every row
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), w.dtype, "gpt2 B=2 N=333")
+    inp = wl.make_inputs(base)                            # full size, sampled rows of sampled sequences
+    rows = [0, 1, 31, 32, 63, 64, 65, 127, 128, 500, 511, 512, 777, 1022, 1023]
+    y = run_forward(base, inp)
+    ref = oracle_forward(base, inp, rows=rows, batches=[0, 5, 7])
+    check(y[[0, 5, 7]][:, rows], ref, base.dtype, "gpt2 full")
+
+
+def test_config3_vit_b_scaled_full_and_full_size_sampled():
+    base = wl.WORKLOADS["vit_b"]
+    w = wl.scaled(base, B=3)
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), w.dtype, "vit B=3")
+    inp = wl.make_inputs(base)
+    y = run_forward(base, inp)
+    batches = [0, 100, 255]
+    rows = [0, 1, 63, 64, 100, 128, 195, 196]
+    ref = oracle_forward(base, inp, rows=rows, batches=batches)
+    check(y[batches][:, rows], ref, base.dtype, "vit full")
+
+
+def test_config4_llama_scaled_full_and_full_size_sampled():
+    base = wl.WORKLOADS["llama7b_n4096"]
+    w = wl.scaled(base, B=1, N=448)
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), w.dtype, "llama B=1 N=448")
+    inp = wl.make_inputs(base)
+    y = run_forward(base, inp)
+    rows = [0, 1, 63, 64, 65, 1000, 2047, 2048, 3000, 4031, 4032, 4094, 4095]
+    ref = oracle_forward(base, inp, rows=rows)
+    check(y[:, rows], ref, base.dtype, "llama full")
+
+
+def run_decode(w, inp):
+    with Layer(w, inp, max_positions=int(max(inp["kv_len"])) + 1) as layer:
+        x = to_device(inp["X"][:, 0], w.dtype)
+        Kc, Vc = to_device(inp["Kcache"], w.dtype), to_device(inp["Vcache"], w.dtype)
+        y = layer.decode(x, Kc, Vc, inp["kv_len"])
+        torch.cuda.synchronize()
+        return to_host(y), to_host(Kc), to_host(Vc)
+
+
+def check_decode(w, inp, what):
+    y, Kc, Vc = run_decode(w, inp)
+    y_ref, K_ref, V_ref = orc.decode_step(inp["X"][:, 0], inp["Kcache"], inp["Vcache"], inp["kv_len"],
+                                          wl.weights_of(inp), w.d_head, w.rope_base)
+    check(y, y_ref, w.dtype, what)
+    for b in range(w.B):
+        L = int(inp["kv_len"][b])
+        check(Kc[b, L - 1], K_ref[b, L - 1], w.dtype, what + " new key row")
+        check(Vc[b, L - 1], V_ref[b, L - 1], w.dtype, what + " new value row")
+        assert np.array_equal(Kc[b, : L - 1], inp["Kcache"][b, : L - 1])      # old rows untouched
+        assert np.array_equal(Vc[b, : L - 1], inp["Vcache"][b, : L - 1])
+
+
+def test_config5_decode_scaled_and_full_size():
+    base = wl.WORKLOADS["decode_32k"]
+    w = wl.scaled(base, B=3, kv_len=700)
+    inp = wl.make_inputs(w)
+    inp["kv_len"] = np.array([700, 1, 449], dtype=np.int32)                 # ragged lengths, a length-1 cache
+    check_decode(w, inp, "decode B=3 ragged")
+    inp = wl.make_inputs(base)
+    check_decode(base, inp, "decode full")
+
+
+# ---- edge cases ----------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 129])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sequence_lengths_around_tile_edges(N, dtype):
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=N, dtype=dtype, seed=100 + N)
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), dtype, f"N={N}")
+
+
+@pytest.mark.parametrize("causal,rope", [(False, 1e4), (False, None), (True, None)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mask_and_rope_switches(causal, rope, dtype):
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=150, dtype=dtype, causal=causal, rope_base=rope, seed=7)
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), dtype, f"causal={causal} rope={rope}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_unequal_and_unaligned_ranks_and_odd_head_count(dtype):
+    # r2 != r3, tilde ranks differ from the plain ones, none a multiple of 32, 3 heads
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=100, n_heads=3, d_model=264, d_head=88, r1=3, r2=40, r3=24,
+                  rt1=2, rt2=72, rt3=56, dtype=dtype, seed=9, recipe="fan_in")
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), dtype, "odd ranks")
+    # wide query/output ranks, 128-wide key/value ranks
+    w = wl.scaled(w, n_heads=5, r1=4, r2=160, r3=128, rt1=4, rt2=96, rt3=128, seed=10)
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), dtype, "wide ranks")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_position_offset_and_cache_outputs(dtype):
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=90, dtype=dtype, seed=11)
+    inp = wl.make_inputs(w)
+    y0 = run_forward(w, inp, pos0=0)
+    y, Kc, Vc = run_forward(w, inp, pos0=37, with_cache=True, Lmax=160)
+    ref = oracle_forward(w, inp, pos0=37)
+    check(y, ref, dtype, "pos0=37")
+    check(y, y0, dtype, "relative-position invariance on the GPU")
+    K_ref, V_ref = orc.latent_kv(inp["X"], wl.weights_of(inp), w.rope_base, pos0=37)
+    check(Kc[:, 37:127], K_ref, dtype, "cache keys")
+    check(Vc[:, 37:127], V_ref, dtype, "cache values")
+    assert np.all(Kc[:, :37] == 0) and np.all(Kc[:, 127:] == 0) and np.all(Vc[:, :37] == 0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sharp_softmax(dtype):
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=1, N=200, dtype=dtype, seed=12)
+    inp = wl.make_inputs(w)
+    inp["C"] = wl.round_to_storage(inp["C"] * 24.0, dtype)                   # scores of tens: near one-hot rows
+    check(run_forward(w, inp), oracle_forward(w, inp), dtype, "sharp softmax")
+
+
+def test_results_are_deterministic():
+    w = wl.scaled(wl.WORKLOADS["gpt2_small"], B=2, N=200)
+    inp = wl.make_inputs(w)
+    a, b = run_forward(w, inp), run_forward(w, inp)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_decode_continues_a_prefill(dtype):
+    # prefill N-1 tokens with cache outputs, then decode token N-1: equals row N-1 of a causal
+    # prefill of all N tokens (oracle) -- the KV-caching identity, across both entry points
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=97, dtype=dtype, seed=13)
+    inp = wl.make_inputs(w)
+    ref = oracle_forward(w, inp, rows=[w.N - 1])
+    with Layer(w, inp, max_positions=128) as layer:
+        X = to_device(inp["X"], dtype)
+        Kc = torch.zeros((w.B, 128, w.r3), dtype=X.dtype, device="cuda")
+        Vc = torch.zeros_like(Kc)
+        layer.forward(X[:, : w.N - 1].contiguous(), Kc=Kc, Vc=Vc)
+        y = layer.decode(X[:, w.N - 1].contiguous(), Kc, Vc, [w.N] * w.B)
+        torch.cuda.synchronize()
+        check(to_host(y), ref[:, 0], dtype, "decode after prefill")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_decode_edge_lengths_and_many_heads(dtype):
+    base = wl.scaled(wl.WORKLOADS["decode_32k"], d_model=256, n_heads=40, d_head=32, r1=4, r2=64, r3=64,
+                     dtype=dtype, B=5, kv_len=200, seed=14)
+    inp = wl.make_inputs(base)
+    inp["kv_len"] = np.array([200, 64, 65, 1, 129], dtype=np.int32)
+    check_decode(base, inp, "decode 40 heads")
+
+
+def test_gpu_side_argument_errors():
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], N=32)
+    inp = wl.make_inputs(w)
+    with Layer(w, inp, max_positions=64) as layer:
+        X = to_device(inp["X"], w.dtype)
+        Y = torch.empty_like(X)
+        ws = layer.workspace(ta.tucker_attn_workspace_bytes(layer.ctx, 1, 32))
+        assert ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, 40, None, None, ws, check=False) == -1
+        assert ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, 0, None, None, ws[:512], check=False) == -3
+        assert ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, 0, None, None, ws, check=True) == 0
+        torch.cuda.synchronize()
