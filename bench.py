@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the Tucker-attention forward hot path on one MI355X.
+
+One "step" = one call of the whole path (weight prep, factor projection, latent RoPE, fused
+attention, head merge, output projection) on one batch of synthetic input that is already
+resident in HBM.  Default workload: the LLaMA-7B-shaped causal layer at N=4096 (bf16).
+Prints ONE JSON line on stdout; progress and the per-kernel table go to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def flops(w, N=None, B=None):
+    """Algorithmic FLOPs of one forward (multiply-add = 2), per step of the path.
+    The per-head query and the head merge are counted in their cheaper form factored through
+    the head rank r1; causal attention counts only visible pairs."""
+    B = w.B if B is None else B
+    N = w.N if N is None else N
+    rt1, rt2, rt3 = w.ranks_post()
+    d, nH = w.d_model, w.n_heads
+    if w.mode == "decode":
+        T = B
+        pairs = w.kv_len
+    else:
+        T = B * N
+        pairs = N * (N + 1) // 2 if w.causal else N * N
+    proj = 2 * T * d * (w.r2 + w.r3 + rt3)
+    qhat = min(2 * T * nH * w.r2 * w.r3, 2 * T * w.r1 * w.r2 * w.r3 + 2 * T * nH * w.r1 * w.r3)
+    attn = B * nH * pairs * (2 * w.r3 + 2 * rt3)
+    merge = min(2 * T * nH * rt2 * rt3, 2 * T * rt1 * rt2 * rt3 + 2 * T * nH * rt1 * rt3)
+    out = 2 * T * rt2 * d
+    return dict(proj=proj, qhat=qhat, attn=attn, merge=merge, out=out,
+                total=proj + qhat + attn + merge + out)
+
+
+def mandatory_bytes(w):
+    es = 2 if w.dtype == "bf16" else 4
+    rt1, rt2, rt3 = w.ranks_post()
+    wts = (w.r1 * w.r2 * w.r3 + rt1 * rt2 * rt3 + w.n_heads * (w.r1 + rt1)
+           + w.d_model * (w.r2 + w.r3 + rt2 + rt3)) * es
+    if w.mode == "decode":
+        return w.B * w.kv_len * (w.r3 + rt3) * es + wts + 2 * w.B * w.d_model * es
+    return 2 * w.B * w.N * w.d_model * es + wts
+
+
+def cpu_baseline(w):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    from oracle import tucker_oracle as orc
+    from paper_2603_30033_amd import workloads as wl
+    if w.mode == "decode":
+        ws = wl.scaled(w, B=2)
+        inp = wl.make_inputs(ws)
+        t0 = time.perf_counter()
+        orc.decode_step(inp["X"][:, 0], inp["Kcache"], inp["Vcache"], inp["kv_len"], wl.weights_of(inp),
+                        ws.d_head, ws.rope_base)
+        dt = time.perf_counter() - t0
+        f = flops(ws)["total"]
+        sample = f"decode step of {ws.B} of the {w.B} sequences at kv_len={w.kv_len} (cache given, as for the GPU)"
+    else:
+        n = min(w.N, 2048)
+        b = 1 if w.N >= 1024 else min(w.B, 16)
+        ws = wl.scaled(w, B=b, N=n)
+        inp = wl.make_inputs(ws)
+        t0 = time.perf_counter()
+        orc.per_head_forward(inp["X"], wl.weights_of(inp), ws.d_head, ws.causal, ws.rope_base)
+        dt = time.perf_counter() - t0
+        f = flops(ws)["total"]
+        sample = f"full oracle forward of {b} sequence(s) of {n} tokens of the same layer shape"
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": f / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": sample, "seconds": round(dt, 3)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="llama7b_n4096")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py measures the one-GPU hot path only; run it with --gpus 1 "
+            "(how the path would shard across GPUs is described in DESIGN.md)")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2603_30033_amd import binding as ta
+    from paper_2603_30033_amd import workloads as wl
+    from paper_2603_30033_amd.device import Layer, to_device
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    log(f"generating {w.name} ...")
+    inp = wl.make_inputs(w)
+    K, W = args.steps, args.warmup
+    fl = flops(w)
+
+    with Layer(w, inp) as layer:
+        if w.mode == "decode":
+            x = to_device(inp["X"][:, 0], w.dtype)
+            y = torch.empty_like(x)
+            # three cache copies in rotation so that a step streams its cache from HBM, not from
+            # the last-level cache that the previous step filled
+            caches = [(to_device(inp["Kcache"], w.dtype), to_device(inp["Vcache"], w.dtype)) for _ in range(3)]
+            lens = [int(v) for v in inp["kv_len"]]
+            ws = layer.workspace(ta.tucker_attn_decode_workspace_bytes(layer.ctx, w.B))
+            step_i = [0]
+
+            def step():
+                kc, vc = caches[step_i[0] % 3]
+                step_i[0] += 1
+                ta.tucker_attn_decode(layer.ctx, layer.weights, x, y, kc, vc, lens, ws)
+            units = w.B
+        else:
+            X = to_device(inp["X"], w.dtype)
+            Y = torch.empty_like(X)
+            ws = layer.workspace(ta.tucker_attn_workspace_bytes(layer.ctx, w.B, w.N))
+
+            def step():
+                ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, w.pos0, None, None, ws)
+            units = w.B * w.N
+
+        for _ in range(W):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ms = dt / K * 1e3
+
+        # per-kernel durations: the same K steps again with HIP events around every launch
+        ta.tucker_attn_profile_enable(layer.ctx, True)
+        acc = {}
+        order = []
+        for _ in range(K):
+            step()
+            for name, t in ta.tucker_attn_profile_read(layer.ctx):
+                if name not in acc:
+                    acc[name] = 0.0
+                    order.append(name)
+                acc[name] += t
+        ta.tucker_attn_profile_enable(layer.ctx, False)
+        kern_ms = {n: acc[n] / K for n in order}
+
+    tflops = fl["total"] / (ms * 1e-3) / 1e12
+    log(f"{w.name}: {ms:.4f} ms/step, {tflops:.1f} TFLOP/s algorithmic, {units / (ms * 1e-3):.3e} tokens/s")
+    for n in order:
+        log(f"  {n:20s} {kern_ms[n] * 1e3:9.1f} us")
+    log(f"  sum of kernels       {sum(kern_ms.values()) * 1e3:9.1f} us")
+
+    if w.mode == "decode":
+        dom = "decode_attention"
+        es = 2 if w.dtype == "bf16" else 4
+        rt3 = w.ranks_post()[2]
+        alg_bytes = w.B * w.kv_len * (w.r3 + rt3) * es
+        ach = alg_bytes / (kern_ms[dom] * 1e-3) / 1e9
+        roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_us": kern_ms[dom] * 1e3}
+    else:
+        dom = "attention"
+        peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS
+        ach = (fl["attn"] + fl["qhat"]) / (kern_ms[dom] * 1e-3) / 1e12
+        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                "frac": ach / peak, "traffic": None, "avg_us": kern_ms[dom] * 1e3}
+
+    out = {
+        "metric": "tucker_attn_fwd_tflops" if w.mode != "decode" else "tucker_attn_decode_tflops",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "N": w.N if w.mode != "decode" else w.kv_len,
+                   "d_model": w.d_model, "n_heads": w.n_heads, "d_head": w.d_head,
+                   "ranks": [w.r1, w.r2, w.r3], "causal": w.causal, "rope_base": w.rope_base, "mode": w.mode},
+        "tokens_per_s": units / (ms * 1e-3),
+        "pct_mfma_peak": 100.0 * tflops / (PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS),
+        "hbm_gbs_mandatory": mandatory_bytes(w) / (ms * 1e-3) / 1e9,
+        "algorithmic_gflop": fl["total"] / 1e9,
+        "kernel_us": {n: kern_ms[n] * 1e3 for n in order},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
