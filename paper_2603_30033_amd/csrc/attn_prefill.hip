@@ -28,9 +28,11 @@ template <typename T, int D, int BC> struct AttnLds {
   static constexpr size_t kBytes = 2ul * kStageElems * sizeof(T);
 };
 
-template <typename T, int D, int QB, int BC>
-__global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs p) {
-  constexpr int CB = D / 32, NB = BC / 32, TQ = 32 * QB;
+template <typename T, int D, int QB, int BC, int QW, int HW>
+__global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) {
+  // QW x HW waves: wave (qw, hw) owns 32*QB queries of one head; the workgroup covers
+  // TQ = 32*QB*QW consecutive tokens of HW heads
+  constexpr int CB = D / 32, NB = BC / 32, TQ = 32 * QB * QW, NT = 64 * QW * HW;
   constexpr int CE = 16 / sizeof(T);                            // elements per 16-byte chunk
   using L = AttnLds<T, D, BC>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -41,10 +43,11 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs p) {
   const int n_qtiles = (p.N + TQ - 1) / TQ;
   const int qt = n_qtiles - 1 - blockIdx.x;                     // heavy (late) query tiles first
   const int b = blockIdx.z;
-  const int head_raw = blockIdx.y * 4 + wave;
+  const int head_raw = blockIdx.y * HW + wave / QW;
   const bool head_ok = head_raw < p.nH;
   const int head = head_ok ? head_raw : p.nH - 1;
-  const int t0 = qt * TQ;
+  const int t0 = qt * TQ;                                       // first token of the workgroup
+  const int tw = t0 + (wave % QW) * 32 * QB;                    // first token of this wave
   const long tok_base = (long)b * p.Npad;
 
   // ---- prologue: Qhat^T = Gt_i * Qlat^T, RoPE, -> B-operand fragments ---------------------
@@ -63,7 +66,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs p) {
       Frag<T> xq[QB];
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
-        int m = t0 + 32 * qb + lr;                              // < Npad because Npad % 64 == 0
+        int m = tw + 32 * qb + lr;                              // < Npad because Npad % 64 == 0
         xq[qb] = load_frag<T>(Ql + (tok_base + m) * p.R2 + bb * 32 + 16 * h);
       }
 #pragma unroll
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs p) {
     if (p.rope != nullptr) {
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
-        int m = t0 + 32 * qb + lr;
+        int m = tw + 32 * qb + lr;
         if (m < p.N) {
           const float2* tab = p.rope + (long)(p.pos0 + m) * (p.r3 / 2);
 #pragma unroll
@@ -121,8 +124,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs p) {
 
   // cooperative staging: K tile = BC rows x D, V^T tile = D rows x BC
   constexpr int KCH = BC * D / CE, VCH = D * BC / CE;           // 16-byte chunks
-  constexpr int KPT = KCH / 256, VPT = VCH / 256;
-  static_assert(KCH % 256 == 0 && VCH % 256 == 0, "tile must fill all threads");
+  constexpr int KPT = (KCH + NT - 1) / NT, VPT = (VCH + NT - 1) / NT;
+  constexpr bool KFULL = KCH % NT == 0, VFULL = VCH % NT == 0;  // else the last round is partial
   constexpr int KCPR = D / CE, VCPR = BC / CE;                  // chunks per row
   const T* Kg = static_cast<const T*>(p.Kr) + tok_base * D;
   const T* Vg = static_cast<const T*>(p.Vt) + (long)b * D * p.Npad;
@@ -131,15 +134,15 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs p) {
     const int n0 = tile * BC;
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
-      int ci = threadIdx.x + i * 256;
+      int ci = threadIdx.x + i * NT;
       int row = ci / KCPR, cc = ci % KCPR;
-      kreg[i] = *reinterpret_cast<const u32x4*>(Kg + (long)(n0 + row) * D + cc * CE);
+      if (KFULL || ci < KCH) kreg[i] = *reinterpret_cast<const u32x4*>(Kg + (long)(n0 + row) * D + cc * CE);
     }
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
-      int ci = threadIdx.x + i * 256;
+      int ci = threadIdx.x + i * NT;
       int row = ci / VCPR, cc = ci % VCPR;
-      vreg[i] = *reinterpret_cast<const u32x4*>(Vg + (long)row * p.Npad + n0 + cc * CE);
+      if (VFULL || ci < VCH) vreg[i] = *reinterpret_cast<const u32x4*>(Vg + (long)row * p.Npad + n0 + cc * CE);
     }
   };
   auto s_store = [&](int stage) {
@@ -147,15 +150,15 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs p) {
     T* vs = ks + L::kKElems;
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
-      int ci = threadIdx.x + i * 256;
+      int ci = threadIdx.x + i * NT;
       int row = ci / KCPR, cc = ci % KCPR;
-      *reinterpret_cast<u32x4*>(ks + row * L::kKRowElems + cc * CE) = kreg[i];
+      if (KFULL || ci < KCH) *reinterpret_cast<u32x4*>(ks + row * L::kKRowElems + cc * CE) = kreg[i];
     }
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
-      int ci = threadIdx.x + i * 256;
+      int ci = threadIdx.x + i * NT;
       int row = ci / VCPR, cc = ci % VCPR;
-      *reinterpret_cast<u32x4*>(vs + row * L::kVRowElems + cc * CE) = vreg[i];
+      if (VFULL || ci < VCH) *reinterpret_cast<u32x4*>(vs + row * L::kVRowElems + cc * CE) = vreg[i];
     }
   };
 
@@ -192,7 +195,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs p) {
     if (need_mask) {
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
-        const int m = t0 + 32 * qb + lr;
+        const int m = tw + 32 * qb + lr;
         const int lim = p.causal ? min(m, p.N - 1) : p.N - 1;   // last visible key
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -257,7 +260,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs p) {
     T* O = static_cast<T*>(p.O);
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      const int m = t0 + 32 * qb + lr;
+      const int m = tw + 32 * qb + lr;
       const float l_tot = halves_sum(l_run[qb]);
       const float inv = 1.f / l_tot;
       if (m < p.N) {
@@ -273,12 +276,12 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs p) {
   }
 }
 
-template <typename T, int D, int QB, int BC>
+template <typename T, int D, int QB, int BC, int QW, int HW>
 static hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
-  constexpr int TQ = 32 * QB;
-  dim3 grid((a.N + TQ - 1) / TQ, (a.nH + 3) / 4, a.Bsz);
+  constexpr int TQ = 32 * QB * QW;
+  dim3 grid((a.N + TQ - 1) / TQ, (a.nH + HW - 1) / HW, a.Bsz);
   size_t smem = AttnLds<T, D, BC>::kBytes;
-  auto kern = attn_prefill_kernel<T, D, QB, BC>;
+  auto kern = attn_prefill_kernel<T, D, QB, BC, QW, HW>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -286,22 +289,22 @@ static hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, a);
+  hipLaunchKernelGGL(kern, grid, dim3(64 * QW * HW), smem, s, a);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_prefill(int dtype, const AttnArgs& a, hipStream_t s) {
   if (dtype == 0) {
     switch (a.D) {
-      case 32: return launch_one<float, 32, 1, 32>(a, s);
-      case 64: return launch_one<float, 64, 1, 32>(a, s);
-      case 128: return launch_one<float, 128, 1, 32>(a, s);
+      case 32: return launch_one<float, 32, 1, 32, 2, 4>(a, s);
+      case 64: return launch_one<float, 64, 1, 32, 2, 4>(a, s);
+      case 128: return launch_one<float, 128, 1, 32, 2, 4>(a, s);
     }
   } else {
     switch (a.D) {
-      case 32: return launch_one<bf16, 32, 2, 64>(a, s);
-      case 64: return launch_one<bf16, 64, 2, 64>(a, s);
-      case 128: return launch_one<bf16, 128, 2, 64>(a, s);
+      case 32: return launch_one<bf16, 32, 1, 64, 2, 4>(a, s);
+      case 64: return launch_one<bf16, 64, 1, 64, 2, 4>(a, s);
+      case 128: return launch_one<bf16, 128, 1, 64, 2, 4>(a, s);
     }
   }
   return hipErrorInvalidValue;
