@@ -41,9 +41,12 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int h = lane / 32, lr = lane % 32;
   const int n_qtiles = (p.N + TQ - 1) / TQ;
-  const int qt = n_qtiles - 1 - blockIdx.x;                     // heavy (late) query tiles first
-  const int b = blockIdx.z;
-  const int head_raw = blockIdx.y * HW + wave / QW;
+  // blockIdx.x = (head group, sequence) varies fastest, blockIdx.y = query tile: workgroups are
+  // dispatched heavy (late causal tiles) first, and those running together read the same keys
+  const int qt = n_qtiles - 1 - blockIdx.y;
+  const int n_hg = (p.nH + HW - 1) / HW;
+  const int b = blockIdx.x / n_hg;
+  const int head_raw = (blockIdx.x % n_hg) * HW + wave / QW;
   const bool head_ok = head_raw < p.nH;
   const int head = head_ok ? head_raw : p.nH - 1;
   const int t0 = qt * TQ;                                       // first token of the workgroup
@@ -106,11 +109,16 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
   }
 
   // ---- main loop over key tiles ----------------------------------------------------------
+  // Online softmax with a lazily updated reference exponent: probabilities are formed as
+  // exp2(s - m_ref) where m_ref is the row maximum seen when it was last refreshed; it is
+  // refreshed (and O, l rescaled) only when a tile's maximum exceeds it by more than kLazy, so
+  // the common tile does no rescaling.  Values stay below 2^kLazy; the final O / l is exact.
+  constexpr float kLazy = 8.f;
   f32x16 oacc[QB][CB];
-  float m_run[QB], l_run[QB];
+  float m_ref[QB], l_run[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    m_run[qb] = -INFINITY;
+    m_ref[qb] = 0.f;
     l_run[qb] = 0.f;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
@@ -217,27 +225,24 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
 #pragma unroll
         for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[qb][nb][e]);
       mx = halves_max(mx);
-      const float m_new = fmaxf(m_run[qb], mx);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = fast_exp2(m_run[qb] - m_use);
-      m_run[qb] = m_new;
-      float rs = 0.f;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float pv = fast_exp2(s[qb][nb][e] - m_use);
-          s[qb][nb][e] = pv;
-          rs += pv;
-        }
-        pf[qb][nb] = to_frag<T>(s[qb][nb]);
-      }
-      l_run[qb] = l_run[qb] * alpha + rs;
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0ull) {
+      const bool upd = (tile == 0 || mx - m_ref[qb] > kLazy) && mx != -INFINITY;
+      if (__builtin_amdgcn_ballot_w64(upd) != 0ull) {
+        const float m_new = upd ? mx : m_ref[qb];
+        const float alpha = fast_exp2(m_ref[qb] - m_new);       // tile 0: O and l are still zero
+        m_ref[qb] = m_new;
+        l_run[qb] *= alpha;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
           for (int e = 0; e < 16; ++e) oacc[qb][cb][e] *= alpha;
+      }
+      const float mr = m_ref[qb];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[qb][nb][e] = fast_exp2(s[qb][nb][e] - mr);
+        pf[qb][nb] = to_frag<T>(s[qb][nb]);
+        l_run[qb] = frag_sum(pf[qb][nb], l_run[qb]);
       }
     }
 
@@ -279,7 +284,7 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
 template <typename T, int D, int QB, int BC, int QW, int HW>
 static hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
   constexpr int TQ = 32 * QB * QW;
-  dim3 grid((a.N + TQ - 1) / TQ, (a.nH + HW - 1) / HW, a.Bsz);
+  dim3 grid(((a.nH + HW - 1) / HW) * a.Bsz, (a.N + TQ - 1) / TQ);
   size_t smem = AttnLds<T, D, BC>::kBytes;
   auto kern = attn_prefill_kernel<T, D, QB, BC, QW, HW>;
   static bool attr_done = false;

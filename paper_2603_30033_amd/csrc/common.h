@@ -132,6 +132,26 @@ __device__ __forceinline__ void store1(bf16* p, float a) { *p = (bf16)a; }
 __device__ __forceinline__ float to_f32(float a) { return a; }
 __device__ __forceinline__ float to_f32(bf16 a) { return (float)a; }
 
+// acc + sum of the 16 elements of a fragment (for bf16: of the rounded values, two per dot2)
+__device__ __forceinline__ float frag_sum(const Frag<float>& f, float acc) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc += f.v[i][j];
+  return acc;
+}
+__device__ __forceinline__ float frag_sum(const Frag<bf16>& f, float acc) {
+  const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      bf16x2 pr = {f.v[i][2 * j], f.v[i][2 * j + 1]};
+      acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
+    }
+  return acc;
+}
+
 // 16-byte chunk of T elements
 template <typename T> struct Chunk { static constexpr int kElems = 16 / sizeof(T); };
 
