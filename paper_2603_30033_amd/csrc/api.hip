@@ -150,8 +150,11 @@ PrepArgs make_prep(const tucker_attn_ctx* c, const tucker_attn_weights* w, void*
   return pa;
 }
 
-int pick_tile_n(int m_tiles, long TP) {
-  if ((long)m_tiles * ((TP + 127) / 128) >= 256) return 128;
+// Token-tile width of a GEMM launch.  A 128-wide tile pays only where the contraction is long
+// (operand re-reads dominate) and the grid still gives every compute unit two workgroups; short
+// contractions are bound by their output stores and run best with more, smaller workgroups.
+int pick_tile_n(int m_tiles, long TP, int K) {
+  if (K >= 1024 && (long)m_tiles * ((TP + 127) / 128) >= 512) return 128;
   if ((long)m_tiles * ((TP + 63) / 64) >= 256) return 64;
   return 32;
 }
@@ -290,7 +293,7 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
   g.Qlat = ws.Qlat; g.R2 = c->R2; g.Kr = ws.Kr; g.D = c->D; g.Vt = ws.Vt;
   g.Kcache = Kcache_out; g.Vcache = Vcache_out; g.Lmax = Lmax; g.r3 = f.r3; g.rt3 = f.rt3;
   g.rope = c->rope; g.pos0 = pos0; g.decode = 0; g.ksplit = 1;
-  if (launch_gemm(f.dtype, g, pick_tile_n((g.M + 127) / 128, TP), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  if (launch_gemm(f.dtype, g, pick_tile_n((g.M + 127) / 128, TP, g.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
   rec.after("factor_projection");
 
   AttnArgs a;
@@ -307,7 +310,7 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
   z.Bsrc = ws.O; z.ldb = (long)f.n_heads * c->D; z.K = f.n_heads * c->D;
   z.Bsz = B; z.N = N; z.Npad = Npad; z.src_padded = 1;
   z.epi = 1; z.Out = ws.Z; z.ldo = c->RT2; z.ksplit = 1; z.R2 = 0; z.D = 0;
-  if (launch_gemm(f.dtype, z, pick_tile_n((z.M + 127) / 128, TP), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  if (launch_gemm(f.dtype, z, pick_tile_n((z.M + 127) / 128, TP, z.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
   rec.after("latent_merge");
 
   GemmArgs y;
@@ -316,7 +319,7 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
   y.Bsrc = ws.Z; y.ldb = c->RT2; y.K = c->RT2;
   y.Bsz = B; y.N = N; y.Npad = Npad; y.src_padded = 1;
   y.epi = 2; y.Out = Y; y.ldo = f.d_model; y.ksplit = 1;
-  if (launch_gemm(f.dtype, y, pick_tile_n((y.M + 127) / 128, TP), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  if (launch_gemm(f.dtype, y, pick_tile_n((y.M + 127) / 128, TP, y.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
   rec.after("output_projection");
   return TUCKER_ATTN_OK;
 }

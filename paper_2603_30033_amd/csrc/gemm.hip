@@ -12,6 +12,8 @@
 // Tiling: workgroup = 4 waves, tile TM x TN (weights x tokens), contraction staged through
 // LDS in slices of 64 elements, double buffered; LDS rows are padded by 16 bytes so that
 // the 16-byte fragment reads of 8 consecutive rows fall into distinct bank groups.
+#include <type_traits>
+
 #include "common.h"
 #include "params.h"
 
@@ -32,8 +34,8 @@ template <typename T, int ROWS> struct Stager {
   static constexpr int kChunks = ROWS * Lds<T>::kChunksPerRow;
   static constexpr int kPerThread = (kChunks + 255) / 256;
   static_assert(kChunks % 256 == 0, "tile rows must fill all threads");
-  u32x4 r[kPerThread];
-  const T* src[kPerThread];   // chunk address at k = 0, null for a zero row
+  struct Regs { u32x4 r[kPerThread]; };   // one slice in flight
+  const T* src[kPerThread];               // chunk address at k = 0, null for a zero row
   int koff[kPerThread];
 
   template <class RowPtr>
@@ -47,20 +49,20 @@ template <typename T, int ROWS> struct Stager {
       src[i] = p ? p + koff[i] : nullptr;
     }
   }
-  __device__ __forceinline__ void load(int k0, int K) {
+  __device__ __forceinline__ void load(Regs& R, int k0, int K) const {
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
       u32x4 v = {0u, 0u, 0u, 0u};
       if (src[i] != nullptr && k0 + koff[i] < K) v = *reinterpret_cast<const u32x4*>(src[i] + k0);
-      r[i] = v;
+      R.r[i] = v;
     }
   }
-  __device__ __forceinline__ void store(T* lds) const {
+  __device__ __forceinline__ void store(const Regs& R, T* lds) const {
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
       int ci = threadIdx.x + i * 256;
       int row = ci / Lds<T>::kChunksPerRow, cc = ci % Lds<T>::kChunksPerRow;
-      *reinterpret_cast<u32x4*>(lds + row * Lds<T>::kRowElems + cc * Lds<T>::kChunkElems) = r[i];
+      *reinterpret_cast<u32x4*>(lds + row * Lds<T>::kRowElems + cc * Lds<T>::kChunkElems) = R.r[i];
     }
   }
 };
@@ -168,6 +170,40 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, in
   }
 }
 
+// Output tile of one wave written as whole rows: accumulators go to a wave-private LDS patch as
+// [token][channel], then 16-byte chunks of consecutive channels are stored, eight rows per
+// instruction (the accumulator layout itself would store 8-byte pieces 8 KB apart).
+template <typename T, int MB, int NB>
+__device__ __forceinline__ void store_rows_y(const GemmArgs& g, const f32x16 (&acc)[MB][NB], T* patch,
+                                             int m_base, int t_base) {
+  constexpr int CW = MB * 32;                                   // channels per patch row
+  constexpr int PRE = CW + 16 / sizeof(T);                      // padded row, elements
+  constexpr int CE = 16 / sizeof(T);
+  constexpr int CPR = CW / CE;                                  // chunks per row
+  const int lane = threadIdx.x % kWave, h = lane / 32, lr = lane % 32;
+  const int TP = g.Bsz * g.Npad;
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        store4(patch + (j * 32 + lr) * PRE + i * 32 + 8 * q + 4 * h, acc[i][j][4 * q], acc[i][j][4 * q + 1],
+               acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+  T* Y = static_cast<T*>(g.Out);
+#pragma unroll
+  for (int it = 0; it < NB * 32 * CPR / kWave; ++it) {
+    const int ci = it * kWave + lane;
+    const int row = ci / CPR, cc = ci % CPR;
+    const int tp = t_base + row, m = m_base + cc * CE;
+    if (tp >= TP || m >= g.M) continue;
+    const int b = tp / g.Npad, n = tp % g.Npad;
+    if (n >= g.N) continue;
+    u32x4 v = *reinterpret_cast<const u32x4*>(patch + row * PRE + cc * CE);
+    *reinterpret_cast<u32x4*>(Y + ((long)b * g.N + n) * g.ldo + m) = v;
+  }
+}
+
 // TM x TN tile, WGM x WGN waves
 template <typename T, int TM, int TN, int WGM, int WGN>
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
@@ -208,26 +244,37 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  // Slices of the contraction travel global -> registers -> LDS.  PF slices are in flight in
+  // registers so that a round trip to memory is hidden behind PF-1 slices of MFMA work.
+  constexpr int PF = sizeof(T) == 2 ? 3 : 2;
   Stager<T, TM> sa;
   Stager<T, TN> sb;
+  typename Stager<T, TM>::Regs ra[PF];
+  typename Stager<T, TN>::Regs rb[PF];
   const int nk_all = (g.K + kKS - 1) / kKS;
   const int per = (nk_all + g.ksplit - 1) / g.ksplit;
   const int ks0 = blockIdx.z * per;
   const int nk = min(nk_all, ks0 + per);
+  const int klim = min(g.K, nk * kKS);                          // nothing is fetched past this split
+  const int cnt = nk - ks0;
+  auto kof = [&](int i) { return i < cnt ? (ks0 + i) * kKS : klim; };
   sa.init(rowA);
   sb.init(rowB);
-  sa.load(ks0 * kKS, g.K);
-  sb.load(ks0 * kKS, g.K);
-  sa.store(stageA(0));
-  sb.store(stageB(0));
+#pragma unroll
+  for (int u = 0; u < PF; ++u) {
+    sa.load(ra[u], kof(u), klim);
+    sb.load(rb[u], kof(u), klim);
+  }
+  sa.store(ra[0], stageA(0));
+  sb.store(rb[0], stageB(0));
   __syncthreads();
 
-  for (int ks = ks0; ks < nk; ++ks) {
+  // one slice: refill the register slot just emptied, multiply from LDS, stage the next slice
+  auto slice = [&](auto slot_c, int ks) {
+    constexpr int S = decltype(slot_c)::value;
     const int cur = (ks - ks0) & 1;
-    if (ks + 1 < nk) {
-      sa.load((ks + 1) * kKS, g.K);
-      sb.load((ks + 1) * kKS, g.K);
-    }
+    sa.load(ra[S], kof(ks - ks0 + PF), klim);
+    sb.load(rb[S], kof(ks - ks0 + PF), klim);
     const T* la = stageA(cur) + (wm * MB * 32 + lr) * RE + 16 * h;
     const T* lb = stageB(cur) + (wn * NB * 32 + lr) * RE + 16 * h;
 #pragma unroll
@@ -243,10 +290,21 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
         for (int j = 0; j < NB; ++j) mma32(acc[i][j], fa[i], fb[j]);
     }
     if (ks + 1 < nk) {
-      sa.store(stageA(cur ^ 1));
-      sb.store(stageB(cur ^ 1));
+      sa.store(ra[(S + 1) % PF], stageA(cur ^ 1));
+      sb.store(rb[(S + 1) % PF], stageB(cur ^ 1));
     }
     __syncthreads();
+  };
+  for (int ks = ks0; ks < nk; ks += PF) {
+    slice(std::integral_constant<int, 0>{}, ks);
+    if (PF > 1 && ks + 1 < nk) slice(std::integral_constant<int, 1 % PF>{}, ks + 1);
+    if (PF > 2 && ks + 2 < nk) slice(std::integral_constant<int, 2 % PF>{}, ks + 2);
+  }
+
+  if (g.epi == 2 && g.ksplit <= 1) {                            // Y: whole rows through LDS
+    constexpr int PatchElems = NB * 32 * (MB * 32 + 16 / sizeof(T));
+    store_rows_y<T, MB, NB>(g, acc, smem + wave * PatchElems, m_tile + wm * MB * 32, t_tile + wn * NB * 32);
+    return;
   }
 
 #pragma unroll
