@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="llama7b_n4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also launch a plain device-to-device copy of this many MiB (three times), so that a "
+                         "hardware-counter run holds a kernel of known HBM traffic to scale its readings by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py measures the one-GPU hot path only; run it with --gpus 1 "
@@ -118,6 +121,14 @@ def main():
     inp = wl.make_inputs(w)
     K, W = args.steps, args.warmup
     fl = flops(w)
+
+    if args.copy_calibration_mib > 0:
+        src = torch.randint(0, 255, (args.copy_calibration_mib << 20,), dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     with Layer(w, inp) as layer:
         if w.mode == "decode":

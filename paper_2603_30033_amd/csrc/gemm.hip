@@ -28,33 +28,43 @@ template <typename T> struct Lds {
   static constexpr int kChunkElems = 16 / sizeof(T);
 };
 
-// Copy a [ROWS x kKS] slice (rows given by a row-pointer functor, null = zero row) into
-// registers / from registers into LDS.  Each thread moves ROWS*chunks/256 16-byte chunks.
+// Copy a [ROWS x kKS] slice of a row-major matrix into registers / from registers into LDS.
+// Each thread moves ROWS*chunks/256 16-byte chunks.  Loads are buffer loads whose range check
+// supplies the zeros: a chunk of a row that does not exist, or past the end of the contraction,
+// gets an offset beyond the descriptor's size.  No load sits behind a branch, so the compiler
+// can keep several slices in flight and wait for exactly the one it stores next.
 template <typename T, int ROWS> struct Stager {
   static constexpr int kChunks = ROWS * Lds<T>::kChunksPerRow;
   static constexpr int kPerThread = (kChunks + 255) / 256;
   static_assert(kChunks % 256 == 0, "tile rows must fill all threads");
-  struct Regs { u32x4 r[kPerThread]; };   // one slice in flight
-  const T* src[kPerThread];               // chunk address at k = 0, null for a zero row
+  static constexpr uint32_t kNone = 0x80000000u;              // offset no descriptor here reaches
+  struct Regs { u32x4 r[kPerThread]; };                        // one slice in flight
+  __amdgpu_buffer_rsrc_t rsrc;
+  uint32_t roff[kPerThread];                                   // byte offset of the chunk at k = 0, or kNone
   int koff[kPerThread];
 
-  template <class RowPtr>
-  __device__ __forceinline__ void init(RowPtr rowptr) {
+  // base: first row of the tile; bytes: extent of the matrix from there on; rowoff(row) gives the
+  // element offset of tile row `row` from base, or -1 for a row of zeros
+  template <class RowOff>
+  __device__ __forceinline__ void init(const T* base, long bytes, RowOff rowoff) {
+    const long lim = 0x7fffffffl;
+    rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(base), 0, (int)(bytes < 0 ? 0 : (bytes > lim ? lim : bytes)),
+                                             0x00020000);
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
       int ci = threadIdx.x + i * 256;
       int row = ci / Lds<T>::kChunksPerRow, cc = ci % Lds<T>::kChunksPerRow;
       koff[i] = cc * Lds<T>::kChunkElems;
-      const T* p = rowptr(row);
-      src[i] = p ? p + koff[i] : nullptr;
+      long ro = rowoff(row);
+      roff[i] = ro < 0 ? kNone : (uint32_t)((ro + koff[i]) * (long)sizeof(T));
     }
   }
   __device__ __forceinline__ void load(Regs& R, int k0, int K) const {
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (src[i] != nullptr && k0 + koff[i] < K) v = *reinterpret_cast<const u32x4*>(src[i] + k0);
-      R.r[i] = v;
+      const bool ok = roff[i] != kNone && k0 + koff[i] < K;
+      const uint32_t off = ok ? roff[i] + (uint32_t)k0 * (uint32_t)sizeof(T) : kNone;
+      R.r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
     }
   }
   __device__ __forceinline__ void store(const Regs& R, T* lds) const {
@@ -216,7 +226,21 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   auto stageA = [&](int s) { return smem + (long)s * (TM + TN) * RE; };
   auto stageB = [&](int s) { return smem + (long)s * (TM + TN) * RE + TM * RE; };
 
-  const int m_tile = blockIdx.x * TM, t_tile = blockIdx.y * TN;
+  // Workgroups go to the eight XCDs round-robin in dispatch order (x fastest).  Remap the index
+  // so that each XCD works through one contiguous range of (token tile, weight tile) pairs: the
+  // weight tiles of one token tile then run on the same XCD back to back, and the token rows
+  // they share are fetched into that XCD's L2 once.
+  int bx = blockIdx.x, by = blockIdx.y;
+  {
+    const int gx = gridDim.x, per = gridDim.x * gridDim.y / 8;
+    const int lin = bx + gx * by;
+    if (lin < per * 8) {
+      const int logical = (lin % 8) * per + lin / 8;
+      bx = logical % gx;
+      by = logical / gx;
+    }
+  }
+  const int m_tile = bx * TM, t_tile = by * TN;
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int wm = wave % WGM, wn = wave / WGM;
   const int h = lane / 32, lr = lane % 32;
@@ -224,16 +248,29 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 
   const T* A = static_cast<const T*>(g.A);
   const T* Bs = static_cast<const T*>(g.Bsrc);
-  auto rowA = [&](int r) -> const T* {
-    int m = m_tile + r;
-    return m < g.M ? A + (long)m * g.lda : nullptr;
-  };
-  auto rowB = [&](int r) -> const T* {
-    int tp = t_tile + r;
-    if (tp >= TP) return nullptr;
-    if (g.src_padded) return Bs + (long)tp * g.ldb;
+  // tile rows as offsets from the tile's first row; rows that do not exist read as zeros
+  const T* baseA = A + (long)m_tile * g.lda;
+  const long bytesA = (long)(g.M - m_tile) * g.lda * (long)sizeof(T);
+  auto rowA = [&](int r) -> long { return m_tile + r < g.M ? (long)r * g.lda : -1l; };
+  // token rows: the workspace copies are padded per sequence, the caller's X is not
+  const long TR = g.src_padded ? (long)TP : (long)g.Bsz * g.N;  // rows the source holds
+  auto src_row = [&](int tp) -> long {                          // source row of padded token tp, -1 if none
+    if (tp >= TP) return -1l;
+    if (g.src_padded) return tp;
     int b = tp / g.Npad, n = tp % g.Npad;
-    return n < g.N ? Bs + ((long)b * g.N + n) * g.ldb : nullptr;
+    return n < g.N ? (long)b * g.N + n : -1l;
+  };
+  long row0 = TR;                                               // first source row the tile touches
+  {
+    const int tp = t_tile < TP ? t_tile : TP;
+    if (g.src_padded) row0 = tp;
+    else if (tp < TP) row0 = (long)(tp / g.Npad) * g.N + min(tp % g.Npad, g.N);
+  }
+  const T* baseB = Bs + row0 * g.ldb;
+  const long bytesB = (TR - row0) * g.ldb * (long)sizeof(T);
+  auto rowB = [&](int r) -> long {
+    long sr = src_row(t_tile + r);
+    return sr < 0 ? -1l : (sr - row0) * g.ldb;
   };
 
   f32x16 acc[MB][NB];
@@ -258,8 +295,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   const int klim = min(g.K, nk * kKS);                          // nothing is fetched past this split
   const int cnt = nk - ks0;
   auto kof = [&](int i) { return i < cnt ? (ks0 + i) * kKS : klim; };
-  sa.init(rowA);
-  sb.init(rowB);
+  sa.init(baseA, bytesA, rowA);
+  sb.init(baseB, bytesB, rowB);
 #pragma unroll
   for (int u = 0; u < PF; ++u) {
     sa.load(ra[u], kof(u), klim);
@@ -267,14 +304,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   }
   sa.store(ra[0], stageA(0));
   sb.store(rb[0], stageB(0));
+  sa.load(ra[0], kof(PF), klim);
+  sb.load(rb[0], kof(PF), klim);
   __syncthreads();
 
-  // one slice: refill the register slot just emptied, multiply from LDS, stage the next slice
+  // One slice: multiply from LDS, then move the next slice from its register slot to the other
+  // LDS stage and refill that slot at once with the slice PF further on.  A slot is never idle,
+  // so its registers are not handed to anything else while a load into them is in flight.
   auto slice = [&](auto slot_c, int ks) {
-    constexpr int S = decltype(slot_c)::value;
+    constexpr int S1 = (decltype(slot_c)::value + 1) % PF;      // slot of slice ks + 1
     const int cur = (ks - ks0) & 1;
-    sa.load(ra[S], kof(ks - ks0 + PF), klim);
-    sb.load(rb[S], kof(ks - ks0 + PF), klim);
     const T* la = stageA(cur) + (wm * MB * 32 + lr) * RE + 16 * h;
     const T* lb = stageB(cur) + (wn * NB * 32 + lr) * RE + 16 * h;
 #pragma unroll
@@ -289,17 +328,23 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 #pragma unroll
         for (int j = 0; j < NB; ++j) mma32(acc[i][j], fa[i], fb[j]);
     }
-    if (ks + 1 < nk) {
-      sa.store(ra[(S + 1) % PF], stageA(cur ^ 1));
-      sb.store(rb[(S + 1) % PF], stageB(cur ^ 1));
-    }
+    // (after the last slice this stages and fetches zeros: cheaper than a branch, behind which
+    // the compiler would have to wait for every load in flight)
+    sa.store(ra[S1], stageA(cur ^ 1));
+    sb.store(rb[S1], stageB(cur ^ 1));
+    sa.load(ra[S1], kof(ks - ks0 + 1 + PF), klim);
+    sb.load(rb[S1], kof(ks - ks0 + 1 + PF), klim);
     __syncthreads();
   };
-  for (int ks = ks0; ks < nk; ks += PF) {
+  // whole groups of PF slices run as one straight-line loop body; the remainder follows
+  int ks = ks0;
+  for (; ks + PF <= nk; ks += PF) {
     slice(std::integral_constant<int, 0>{}, ks);
-    if (PF > 1 && ks + 1 < nk) slice(std::integral_constant<int, 1 % PF>{}, ks + 1);
-    if (PF > 2 && ks + 2 < nk) slice(std::integral_constant<int, 2 % PF>{}, ks + 2);
+    if (PF > 1) slice(std::integral_constant<int, 1 % PF>{}, ks + 1);
+    if (PF > 2) slice(std::integral_constant<int, 2 % PF>{}, ks + 2);
   }
+  if (ks < nk) slice(std::integral_constant<int, 0>{}, ks);
+  if (PF > 2 && ks + 1 < nk) slice(std::integral_constant<int, 1 % PF>{}, ks + 1);
 
   if (g.epi == 2 && g.ksplit <= 1) {                            // Y: whole rows through LDS
     constexpr int PatchElems = NB * 32 * (MB * 32 + 16 / sizeof(T));
