@@ -24,7 +24,7 @@ struct tucker_attn_ctx {
   tucker_attn_config cfg;
   int R2, RT2, D, dp;          // padded ranks, common K/V width, padded d
   int es;                      // bytes per stored element
-  float2* rope;                // device [max_positions][r3/2] or null
+  float2* rope;                // device [max_positions][D/2] (cos, sin) or null
   float qscale;                // log2(e) / sqrt(d_head), folded into the head-mixed core
   int profile;
   int n_kernels;
@@ -216,14 +216,16 @@ int tucker_attn_create(const tucker_attn_config* cfg, tucker_attn_ctx** out) {
   c->qscale = (float)(1.4426950408889634 / std::sqrt((double)f.d_head));
   c->rope = nullptr;
   if (f.use_rope) {
-    // angle = position * base^(-2j/r3), evaluated in double precision, stored as fp32 (cos, sin)
-    const int half = f.r3 / 2;
-    std::vector<float2> tab((size_t)f.max_positions * half);
+    // angle = position * base^(-2j/r3), evaluated in double precision, stored as fp32 (cos, sin).
+    // A table row holds D/2 pairs: the pairs beyond r3/2 belong to padding channels and are the
+    // identity rotation, so the kernels read whole rows without looking at r3.
+    const int half = f.r3 / 2, ld = D / 2;
+    std::vector<float2> tab((size_t)f.max_positions * ld, make_float2(1.f, 0.f));
     for (int j = 0; j < half; ++j) {
       const double theta = std::pow((double)f.rope_base, -2.0 * j / (double)f.r3);
       for (int p = 0; p < f.max_positions; ++p) {
         const double a = (double)p * theta;
-        tab[(size_t)p * half + j] = make_float2((float)std::cos(a), (float)std::sin(a));
+        tab[(size_t)p * ld + j] = make_float2((float)std::cos(a), (float)std::sin(a));
       }
     }
     if (hipMalloc(&c->rope, tab.size() * sizeof(float2)) != hipSuccess) {

@@ -35,18 +35,17 @@ __global__ __launch_bounds__(256) void decode_qhat_kernel(DecodeArgs p) {
         mma32(acc, gf, xq);
       }
       if (p.rope != nullptr && tok < p.Bsz) {
-        const float2* tab = p.rope + (long)(p.kv_len[tok] - 1) * (p.r3 / 2);
+        const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope + (long)(p.kv_len[tok] - 1) * (D / 2) + (cb * 32 + 4 * h) / 2);
+        f32x4 cs[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) cs[q] = tab[2 * q];
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
           for (int e = 0; e < 4; e += 2) {
-            int c = cb * 32 + 8 * q + 4 * h + e;
-            if (c < p.r3) {
-              float2 cs = tab[c / 2];
-              float x0 = acc[4 * q + e], x1 = acc[4 * q + e + 1];
-              acc[4 * q + e] = x0 * cs.x - x1 * cs.y;
-              acc[4 * q + e + 1] = x0 * cs.y + x1 * cs.x;
-            }
+            float x0 = acc[4 * q + e], x1 = acc[4 * q + e + 1];
+            acc[4 * q + e] = x0 * cs[q][e] - x1 * cs[q][e + 1];
+            acc[4 * q + e + 1] = x0 * cs[q][e + 1] + x1 * cs[q][e];
           }
       }
     }

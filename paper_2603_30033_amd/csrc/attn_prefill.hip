@@ -53,83 +53,6 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
   const int tw = t0 + (wave % QW) * 32 * QB;                    // first token of this wave
   const long tok_base = (long)b * p.Npad;
 
-  // ---- prologue: Qhat^T = Gt_i * Qlat^T, RoPE, -> B-operand fragments ---------------------
-  Frag<T> qf[QB][CB];
-  {
-    f32x16 qa[QB][CB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) qa[qb][cb][e] = 0.f;
-    const T* Gt = static_cast<const T*>(p.Gt) + (long)head * D * p.R2;
-    const T* Ql = static_cast<const T*>(p.Qlat);
-    for (int bb = 0; bb < p.R2 / 32; ++bb) {
-      Frag<T> xq[QB];
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        int m = tw + 32 * qb + lr;                              // < Npad because Npad % 64 == 0
-        xq[qb] = load_frag<T>(Ql + (tok_base + m) * p.R2 + bb * 32 + 16 * h);
-      }
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb) {
-        Frag<T> gf = load_frag<T>(Gt + (long)(cb * 32 + lr) * p.R2 + bb * 32 + 16 * h);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) mma32(qa[qb][cb], gf, xq[qb]);
-      }
-    }
-    if (p.rope != nullptr) {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        int m = tw + 32 * qb + lr;
-        if (m < p.N) {
-          const float2* tab = p.rope + (long)(p.pos0 + m) * (p.r3 / 2);
-#pragma unroll
-          for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-              for (int e = 0; e < 4; e += 2) {
-                int c = cb * 32 + 8 * q + 4 * h + e;
-                if (c < p.r3) {
-                  float2 cs = tab[c / 2];
-                  float x0 = qa[qb][cb][4 * q + e], x1 = qa[qb][cb][4 * q + e + 1];
-                  qa[qb][cb][4 * q + e] = x0 * cs.x - x1 * cs.y;
-                  qa[qb][cb][4 * q + e + 1] = x0 * cs.y + x1 * cs.x;
-                }
-              }
-        }
-      }
-    }
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb) qf[qb][cb] = to_frag<T>(qa[qb][cb]);
-  }
-
-  // ---- main loop over key tiles ----------------------------------------------------------
-  // Online softmax with a lazily updated reference exponent: probabilities are formed as
-  // exp2(s - m_ref) where m_ref is the row maximum seen when it was last refreshed; it is
-  // refreshed (and O, l rescaled) only when a tile's maximum exceeds it by more than kLazy, so
-  // the common tile does no rescaling.  Values stay below 2^kLazy; the final O / l is exact.
-  constexpr float kLazy = 8.f;
-  f32x16 oacc[QB][CB];
-  float m_ref[QB], l_run[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m_ref[qb] = 0.f;
-    l_run[qb] = 0.f;
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) oacc[qb][cb][e] = 0.f;
-  }
-
-  // keys needed: causal -> 0 .. t0+TQ-1 (clipped to N), else 0 .. N-1
-  const int kv_end = p.causal ? min(p.N, t0 + TQ) : p.N;
-  const int n_tiles = (kv_end + BC - 1) / BC;
-
   // cooperative staging: K tile = BC rows x D, V^T tile = D rows x BC
   constexpr int KCH = BC * D / CE, VCH = D * BC / CE;           // 16-byte chunks
   constexpr int KPT = (KCH + NT - 1) / NT, VPT = (VCH + NT - 1) / NT;
@@ -170,7 +93,99 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
     }
   };
 
-  g_load(0);
+  g_load(0);                                                   // in flight during the prologue
+
+  // ---- prologue: Qhat^T = Gt_i * Qlat^T, RoPE, -> B-operand fragments ---------------------
+  // The rotation table entries of this lane's token are fetched first and the operand fragments
+  // of the next contraction block are fetched while the current one is multiplied, so that the
+  // prologue pays for about one round trip to memory instead of one per block.
+  Frag<T> qf[QB][CB];
+  {
+    f32x16 qa[QB][CB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) qa[qb][cb][e] = 0.f;
+    f32x4 cs[QB][CB][4];                                        // (cos, sin) of channel pairs 8q+4h+{0,2}
+    if (p.rope != nullptr) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const int m = min(tw + 32 * qb + lr, p.N - 1);          // padding tokens borrow the last row
+        const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope + (long)(p.pos0 + m) * (D / 2) + 2 * h);
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) cs[qb][cb][q] = tab[cb * 8 + 2 * q];
+      }
+    }
+    const T* Gt = static_cast<const T*>(p.Gt) + (long)head * D * p.R2 + (long)lr * p.R2 + 16 * h;
+    const T* Ql = static_cast<const T*>(p.Qlat) + (tok_base + tw + lr) * p.R2 + 16 * h;   // tw+lr < Npad
+    const int nbb = p.R2 / 32;
+    Frag<T> xq[QB], gf[CB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) xq[qb] = load_frag<T>(Ql + (long)32 * qb * p.R2);
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) gf[cb] = load_frag<T>(Gt + (long)cb * 32 * p.R2);
+    for (int bb = 0; bb < nbb; ++bb) {
+      Frag<T> xn[QB], gn[CB];
+      const int nx = min(bb + 1, nbb - 1) * 32;                 // the last block is fetched twice
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) xn[qb] = load_frag<T>(Ql + (long)32 * qb * p.R2 + nx);
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) gn[cb] = load_frag<T>(Gt + (long)cb * 32 * p.R2 + nx);
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) mma32(qa[qb][cb], gf[cb], xq[qb]);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) xq[qb] = xn[qb];
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) gf[cb] = gn[cb];
+    }
+    if (p.rope != nullptr) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; e += 2) {
+              float x0 = qa[qb][cb][4 * q + e], x1 = qa[qb][cb][4 * q + e + 1];
+              qa[qb][cb][4 * q + e] = x0 * cs[qb][cb][q][e] - x1 * cs[qb][cb][q][e + 1];
+              qa[qb][cb][4 * q + e + 1] = x0 * cs[qb][cb][q][e + 1] + x1 * cs[qb][cb][q][e];
+            }
+    }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) qf[qb][cb] = to_frag<T>(qa[qb][cb]);
+  }
+
+  // ---- main loop over key tiles ----------------------------------------------------------
+  // Online softmax with a lazily updated reference exponent: probabilities are formed as
+  // exp2(s - m_ref) where m_ref is the row maximum seen when it was last refreshed; it is
+  // refreshed (and O, l rescaled) only when a tile's maximum exceeds it by more than kLazy, so
+  // the common tile does no rescaling.  Values stay below 2^kLazy; the final O / l is exact.
+  constexpr float kLazy = 8.f;
+  f32x16 oacc[QB][CB];
+  float m_ref[QB], l_run[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    m_ref[qb] = 0.f;
+    l_run[qb] = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[qb][cb][e] = 0.f;
+  }
+
+  // keys needed: causal -> 0 .. t0+TQ-1 (clipped to N), else 0 .. N-1
+  const int kv_end = p.causal ? min(p.N, t0 + TQ) : p.N;
+  const int n_tiles = (kv_end + BC - 1) / BC;
+
   s_store(0);
   __syncthreads();
 

@@ -77,11 +77,6 @@ template <typename T, int ROWS> struct Stager {
   }
 };
 
-template <typename T>
-__device__ __forceinline__ float2 rope_cs(const GemmArgs& g, int pos, int pair) {
-  return g.rope[(long)pos * (g.r3 / 2) + pair];
-}
-
 // ---- epilogues: one 32x32 accumulator block = 32 weight rows (m0..) x 32 tokens ----------
 template <typename T>
 __device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, int m0, int tp) {
@@ -99,18 +94,20 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, in
       store_frag<T>(dst, to_frag<T>(acc));
     } else if (m0 < g.R2 + g.D) {                               // ---- K, rotated
       const int c0 = m0 - g.R2;
-      if (g.rope != nullptr && valid) {
+      if (g.rope != nullptr) {
+        // (cos, sin) of two adjacent pairs per load, all four loads issued before the first use;
+        // rows of padding tokens hold zeros, so any table row serves them
+        const f32x4* tab = reinterpret_cast<const f32x4*>(g.rope + (long)(valid ? pos : 0) * (g.D / 2) + (c0 + 4 * h) / 2);
+        f32x4 cs[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) cs[q] = tab[2 * q];
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
           for (int e = 0; e < 4; e += 2) {
-            int c = c0 + 8 * q + 4 * h + e;
-            if (c < g.r3) {
-              float2 cs = rope_cs<T>(g, pos, c / 2);
-              float x0 = acc[4 * q + e], x1 = acc[4 * q + e + 1];
-              acc[4 * q + e] = x0 * cs.x - x1 * cs.y;
-              acc[4 * q + e + 1] = x0 * cs.y + x1 * cs.x;
-            }
+            float x0 = acc[4 * q + e], x1 = acc[4 * q + e + 1];
+            acc[4 * q + e] = x0 * cs[q][e] - x1 * cs[q][e + 1];
+            acc[4 * q + e + 1] = x0 * cs[q][e + 1] + x1 * cs[q][e];
           }
       }
       if (g.Kr != nullptr) {

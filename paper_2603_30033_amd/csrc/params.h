@@ -50,7 +50,7 @@ struct GemmArgs {
   void* Vt;                     // [B][D][Npad], n in acc order within 32-blocks; null in decode
   void* Kcache; void* Vcache;   // nullable [B][Lmax][r3]/[B][Lmax][rt3], natural order
   int Lmax, r3, rt3;
-  const float2* rope;           // [max_pos][r3/2] (cos, sin) or null
+  const float2* rope;           // [max_pos][D/2] (cos, sin), identity beyond r3/2, or null
   int pos0;
   int decode;                   // 1: one token per sequence, position/cache row from kv_pos[b]
   int kv_pos[32];
