@@ -24,7 +24,7 @@ struct tucker_attn_ctx {
   tucker_attn_config cfg;
   int R2, RT2, D, dp;          // padded ranks, common K/V width, padded d
   int es;                      // bytes per stored element
-  float2* rope;                // device [max_positions][D/2] (cos, sin) or null
+  float4* rope;                // device [D/4][max_positions] (cos, sin, cos, sin) or null
   float qscale;                // log2(e) / sqrt(d_head), folded into the head-mixed core
   int profile;
   int n_kernels;
@@ -111,13 +111,13 @@ DecodeWs carve_decode(const tucker_attn_ctx* c, void* ws, int B) {
 }
 
 void add_job(PrepArgs& pa, const void* src, const void* coef, void* out, int A, int rows, int cols, int Z,
-             int rows_pad, int cols_pad, long sz, long su, int transposed, int perm, float scale) {
+             int rows_pad, int cols_pad, long sz, long su, int transposed, int perm, float scale, int frag = 0) {
   PrepJob& j = pa.job[pa.n_jobs++];
   j.src = src; j.coef = coef; j.out = out;
   j.A = A; j.rows = rows; j.cols = cols; j.Z = Z;
   j.rows_pad = rows_pad; j.cols_pad = cols_pad;
   j.out_stride_z = sz; j.out_stride_u = su;
-  j.transposed = transposed; j.perm = perm; j.scale = scale;
+  j.transposed = transposed; j.perm = perm; j.scale = scale; j.frag = frag;
   j.first_block = pa.total_blocks;
   pa.total_blocks += Z * (rows_pad / 32) * (cols_pad / 32);
 }
@@ -130,8 +130,8 @@ PrepArgs make_prep(const tucker_attn_ctx* c, const tucker_attn_weights* w, void*
   PrepArgs pa;
   std::memset(&pa, 0, sizeof(pa));
   const long nHD = (long)f.n_heads * c->D;
-  // Gt[i][c][b] = qscale * sum_a U1[i,a] C[a,b,c]
-  add_job(pa, w->C, w->U1, Gt, f.r1, f.r2, f.r3, f.n_heads, c->R2, c->D, (long)c->D * c->R2, c->R2, 1, 1, c->qscale);
+  // Gt[i][c][b] = qscale * sum_a U1[i,a] C[a,b,c], fragment-major 32x32 blocks of (c, b)
+  add_job(pa, w->C, w->U1, Gt, f.r1, f.r2, f.r3, f.n_heads, c->R2, c->D, (long)c->D * c->R2, c->R2, 1, 1, c->qscale, 1);
   // Gtil2[b][i*D + c] = sum_a U~1[i,a] C~[a,b,c]
   add_job(pa, w->Ct, w->Ut1, Gtil2, f.rt1, f.rt2, f.rt3, f.n_heads, c->RT2, c->D, c->D, nHD, 0, 1, 1.f);
   // Wcat rows: U2^T | U3^T | U~3^T, each [rank_pad][dp]
@@ -216,23 +216,25 @@ int tucker_attn_create(const tucker_attn_config* cfg, tucker_attn_ctx** out) {
   c->qscale = (float)(1.4426950408889634 / std::sqrt((double)f.d_head));
   c->rope = nullptr;
   if (f.use_rope) {
-    // angle = position * base^(-2j/r3), evaluated in double precision, stored as fp32 (cos, sin).
-    // A table row holds D/2 pairs: the pairs beyond r3/2 belong to padding channels and are the
-    // identity rotation, so the kernels read whole rows without looking at r3.
-    const int half = f.r3 / 2, ld = D / 2;
-    std::vector<float2> tab((size_t)f.max_positions * ld, make_float2(1.f, 0.f));
+    // angle = position * base^(-2j/r3), evaluated in double precision, stored as fp32.  Entry
+    // [k][p] holds (cos, sin) of pairs 2k and 2k+1 at position p; pairs beyond r3/2 belong to
+    // padding channels and are the identity rotation, so the kernels never look at r3.
+    const int half = f.r3 / 2, quads = D / 4;
+    std::vector<float4> tab((size_t)quads * f.max_positions, make_float4(1.f, 0.f, 1.f, 0.f));
     for (int j = 0; j < half; ++j) {
       const double theta = std::pow((double)f.rope_base, -2.0 * j / (double)f.r3);
       for (int p = 0; p < f.max_positions; ++p) {
         const double a = (double)p * theta;
-        tab[(size_t)p * ld + j] = make_float2((float)std::cos(a), (float)std::sin(a));
+        float4& e = tab[(size_t)(j / 2) * f.max_positions + p];
+        if (j % 2 == 0) { e.x = (float)std::cos(a); e.y = (float)std::sin(a); }
+        else { e.z = (float)std::cos(a); e.w = (float)std::sin(a); }
       }
     }
-    if (hipMalloc(&c->rope, tab.size() * sizeof(float2)) != hipSuccess) {
+    if (hipMalloc(&c->rope, tab.size() * sizeof(float4)) != hipSuccess) {
       delete c;
       return TUCKER_ATTN_HIP_ERROR;
     }
-    if (hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice) != hipSuccess) {
+    if (hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(float4), hipMemcpyHostToDevice) != hipSuccess) {
       (void)hipFree(c->rope);
       delete c;
       return TUCKER_ATTN_HIP_ERROR;
@@ -294,13 +296,13 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
   g.epi = 0;
   g.Qlat = ws.Qlat; g.R2 = c->R2; g.Kr = ws.Kr; g.D = c->D; g.Vt = ws.Vt;
   g.Kcache = Kcache_out; g.Vcache = Vcache_out; g.Lmax = Lmax; g.r3 = f.r3; g.rt3 = f.rt3;
-  g.rope = c->rope; g.pos0 = pos0; g.decode = 0; g.ksplit = 1;
+  g.rope = c->rope; g.rope_ld = f.max_positions; g.pos0 = pos0; g.decode = 0; g.ksplit = 1;
   if (launch_gemm(f.dtype, g, pick_tile_n((g.M + 127) / 128, TP, g.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
   rec.after("factor_projection");
 
   AttnArgs a;
   std::memset(&a, 0, sizeof(a));
-  a.Qlat = ws.Qlat; a.Gt = ws.Gt; a.Kr = ws.Kr; a.Vt = ws.Vt; a.O = ws.O; a.rope = c->rope;
+  a.Qlat = ws.Qlat; a.Gt = ws.Gt; a.Kr = ws.Kr; a.Vt = ws.Vt; a.O = ws.O; a.rope = c->rope; a.rope_ld = f.max_positions;
   a.Bsz = B; a.N = N; a.Npad = Npad; a.nH = f.n_heads; a.R2 = c->R2; a.r3 = f.r3; a.D = c->D;
   a.causal = f.causal; a.pos0 = pos0;
   if (launch_attn_prefill(f.dtype, a, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
@@ -361,7 +363,7 @@ int tucker_attn_decode(tucker_attn_ctx* c, const tucker_attn_weights* w, const v
   g.epi = 0;
   g.Qlat = ws.Qlat; g.R2 = c->R2; g.Kr = nullptr; g.D = c->D; g.Vt = nullptr;
   g.Kcache = Kcache; g.Vcache = Vcache; g.Lmax = Lmax; g.r3 = f.r3; g.rt3 = f.rt3;
-  g.rope = c->rope; g.pos0 = 0; g.decode = 1;
+  g.rope = c->rope; g.rope_ld = f.max_positions; g.pos0 = 0; g.decode = 1;
   for (int b = 0; b < B; ++b) g.kv_pos[b] = kv_len[b] - 1;
   g.ksplit = decode_ksplit(g.K); g.part = ws.part;
   if (launch_gemm(f.dtype, g, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
@@ -370,7 +372,7 @@ int tucker_attn_decode(tucker_attn_ctx* c, const tucker_attn_weights* w, const v
   DecodeArgs d;
   std::memset(&d, 0, sizeof(d));
   d.Qlat = ws.Qlat; d.Gt = ws.Gt; d.Qh = ws.Qh; d.Kcache = Kcache; d.Vcache = Vcache;
-  d.part_m = ws.pm; d.part_l = ws.pl; d.part_o = ws.po; d.O = ws.O; d.rope = c->rope;
+  d.part_m = ws.pm; d.part_l = ws.pl; d.part_o = ws.po; d.O = ws.O; d.rope = c->rope; d.rope_ld = f.max_positions;
   d.Bsz = B; d.nH = f.n_heads; d.HB = pad32(f.n_heads) / 32; d.R2 = c->R2; d.r3 = f.r3; d.rt3 = f.rt3;
   d.D = c->D; d.Lmax = Lmax; d.nsplit = decode_nsplit(B);
   for (int b = 0; b < B; ++b) d.kv_len[b] = kv_len[b];

@@ -31,14 +31,14 @@ __global__ __launch_bounds__(256) void decode_qhat_kernel(DecodeArgs p) {
       const T* Ql = static_cast<const T*>(p.Qlat);
       for (int bb = 0; bb < p.R2 / 32; ++bb) {
         Frag<T> xq = tok < p.Bsz ? load_frag<T>(Ql + (long)tok * p.R2 + bb * 32 + 16 * h) : zero_frag<T>();
-        Frag<T> gf = load_frag<T>(Gt + (long)(cb * 32 + tok) * p.R2 + bb * 32 + 16 * h);
+        Frag<T> gf = load_frag_major<T>(Gt + (long)(cb * (p.R2 / 32) + bb) * kFragBlockElems, lane);
         mma32(acc, gf, xq);
       }
       if (p.rope != nullptr && tok < p.Bsz) {
-        const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope + (long)(p.kv_len[tok] - 1) * (D / 2) + (cb * 32 + 4 * h) / 2);
+        const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope) + (long)(cb * 8 + h) * p.rope_ld + (p.kv_len[tok] - 1);
         f32x4 cs[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) cs[q] = tab[2 * q];
+        for (int q = 0; q < 4; ++q) cs[q] = tab[(long)2 * q * p.rope_ld];
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll

@@ -13,7 +13,9 @@
 // partner lane, and accumulators turn into the next product's operand without any
 // cross-lane movement (see the fragment model in common.h).
 //
-// Workgroup = 4 waves = 4 heads x (32*QB) queries; K/V tile = BC keys, double buffered.
+// Workgroup = QW x HW waves = HW heads x (32*QB*QW) queries; K/V tile = BC keys, double buffered.
+#include <type_traits>
+
 #include "common.h"
 #include "params.h"
 
@@ -61,19 +63,18 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
   const T* Kg = static_cast<const T*>(p.Kr) + tok_base * D;
   const T* Vg = static_cast<const T*>(p.Vt) + (long)b * D * p.Npad;
   u32x4 kreg[KPT], vreg[VPT];
-  auto g_load = [&](int tile) {
-    const int n0 = tile * BC;
+  auto g_load = [&](int ktile, int vtile) {                    // K rows of ktile, V^T columns of vtile
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
       int ci = threadIdx.x + i * NT;
       int row = ci / KCPR, cc = ci % KCPR;
-      if (KFULL || ci < KCH) kreg[i] = *reinterpret_cast<const u32x4*>(Kg + (long)(n0 + row) * D + cc * CE);
+      if (KFULL || ci < KCH) kreg[i] = *reinterpret_cast<const u32x4*>(Kg + (long)(ktile * BC + row) * D + cc * CE);
     }
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
       int ci = threadIdx.x + i * NT;
       int row = ci / VCPR, cc = ci % VCPR;
-      if (VFULL || ci < VCH) vreg[i] = *reinterpret_cast<const u32x4*>(Vg + (long)row * p.Npad + n0 + cc * CE);
+      if (VFULL || ci < VCH) vreg[i] = *reinterpret_cast<const u32x4*>(Vg + (long)row * p.Npad + vtile * BC + cc * CE);
     }
   };
   auto s_store = [&](int stage) {
@@ -93,12 +94,12 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
     }
   };
 
-  g_load(0);                                                   // in flight during the prologue
+  g_load(0, 0);                                                // in flight during the prologue
 
   // ---- prologue: Qhat^T = Gt_i * Qlat^T, RoPE, -> B-operand fragments ---------------------
-  // The rotation table entries of this lane's token are fetched first and the operand fragments
-  // of the next contraction block are fetched while the current one is multiplied, so that the
-  // prologue pays for about one round trip to memory instead of one per block.
+  // Operand fragments are fetched two contraction blocks ahead of their product; the rotation
+  // table entries of this lane's token are fetched after the last product, into the registers
+  // the operands leave free.
   Frag<T> qf[QB][CB];
   {
     f32x16 qa[QB][CB];
@@ -108,43 +109,58 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
       for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) qa[qb][cb][e] = 0.f;
-    f32x4 cs[QB][CB][4];                                        // (cos, sin) of channel pairs 8q+4h+{0,2}
-    if (p.rope != nullptr) {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const int m = min(tw + 32 * qb + lr, p.N - 1);          // padding tokens borrow the last row
-        const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope + (long)(p.pos0 + m) * (D / 2) + 2 * h);
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) cs[qb][cb][q] = tab[cb * 8 + 2 * q];
-      }
-    }
-    const T* Gt = static_cast<const T*>(p.Gt) + (long)head * D * p.R2 + (long)lr * p.R2 + 16 * h;
-    const T* Ql = static_cast<const T*>(p.Qlat) + (tok_base + tw + lr) * p.R2 + 16 * h;   // tw+lr < Npad
+    // Gt_i is fragment-major: block (cb, bb) is one contiguous kilobyte-per-load piece
     const int nbb = p.R2 / 32;
-    Frag<T> xq[QB], gf[CB];
+    const T* Gt = static_cast<const T*>(p.Gt) + (long)head * D * p.R2;
+    const T* Ql = static_cast<const T*>(p.Qlat) + (tok_base + tw + lr) * p.R2 + 16 * h;   // tw+lr < Npad
+    // two register sets, filled alternately two contraction blocks ahead (no copies between
+    // them); a block index past the end re-reads the last block, whose product is skipped
+    struct Set { Frag<T> xq[QB], gf[CB]; } sa, sb;
+    auto fetch = [&](Set& st, int bb) {
+      const int bc = min(bb, nbb - 1);
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) xq[qb] = load_frag<T>(Ql + (long)32 * qb * p.R2);
+      for (int qb = 0; qb < QB; ++qb) st.xq[qb] = load_frag<T>(Ql + (long)32 * qb * p.R2 + bc * 32);
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) gf[cb] = load_frag<T>(Gt + (long)cb * 32 * p.R2);
-    for (int bb = 0; bb < nbb; ++bb) {
-      Frag<T> xn[QB], gn[CB];
-      const int nx = min(bb + 1, nbb - 1) * 32;                 // the last block is fetched twice
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) xn[qb] = load_frag<T>(Ql + (long)32 * qb * p.R2 + nx);
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb) gn[cb] = load_frag<T>(Gt + (long)cb * 32 * p.R2 + nx);
+      for (int cb = 0; cb < CB; ++cb) st.gf[cb] = load_frag_major<T>(Gt + (long)(cb * nbb + bc) * kFragBlockElems, lane);
+    };
+    auto multiply = [&](const Set& st) {
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) mma32(qa[qb][cb], gf[cb], xq[qb]);
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) xq[qb] = xn[qb];
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb) gf[cb] = gn[cb];
+        for (int qb = 0; qb < QB; ++qb) mma32(qa[qb][cb], st.gf[cb], st.xq[qb]);
+    };
+    constexpr bool kTwoSets = 2 * sizeof(Set) <= 96 * 4;        // else one set (wide fp32 fragments)
+    fetch(sa, 0);
+    if (kTwoSets) {
+      fetch(sb, 1);
+      for (int bb = 0; bb < nbb; bb += 2) {
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(sa);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(sa, bb + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        if (bb + 1 < nbb) multiply(sb);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(sb, bb + 3);
+      }
+    } else {
+      for (int bb = 0; bb < nbb; ++bb) {
+        multiply(sa);
+        fetch(sa, bb + 1);
+      }
     }
+    __builtin_amdgcn_sched_barrier(0);                          // the table entries reuse the operand registers
     if (p.rope != nullptr) {
+      f32x4 cs[QB][CB][4];                                      // (cos, sin) of channel pairs 8q+4h+{0,2}
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const int m = min(tw + 32 * qb + lr, p.N - 1);          // padding tokens borrow the last row
+        const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope) + (long)h * p.rope_ld + p.pos0 + m;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) cs[qb][cb][q] = tab[(long)(cb * 8 + 2 * q) * p.rope_ld];
+      }
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -186,33 +202,61 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
   const int kv_end = p.causal ? min(p.N, t0 + TQ) : p.N;
   const int n_tiles = (kv_end + BC - 1) / BC;
 
-  s_store(0);
-  __syncthreads();
-
-  for (int tile = 0; tile < n_tiles; ++tile) {
-    const int cur = tile & 1;
-    if (tile + 1 < n_tiles) g_load(tile + 1);
-    const T* ks = smem + (long)cur * L::kStageElems;
-    const T* vs = ks + L::kKElems;
-    const int n0 = tile * BC;
-
-    // S^T = K Qhat^T
-    f32x16 s[QB][NB];
+  // The two waves that share a SIMD (waves w and w+4) go through a key tile in opposite order, so
+  // that one is in its MFMA phase while the other is in its softmax (VALU) phase:
+  //   interval t, waves 0..3:  O += V(t-1) P(t-1);  S = K(t) Qhat;  P(t) = softmax step of S
+  //   interval t, waves 4..7:  P(t-1) = softmax step of S;  O += V(t-1) P(t-1);  S = K(t) Qhat
+  // Both read K(t) and V(t-1) in interval t, so LDS stage t%2 holds exactly that pair, and the
+  // pair of interval t+1 is staged meanwhile; one barrier per interval, n_tiles+1 intervals.
+  f32x16 s[QB][NB];
+  Frag<T> pf[QB][NB];
+  // MFMA phase: O += V(tile-1) P(tile-1) (if PV) and then S = K(tile) Qhat (if SS), as ONE stream
+  // of operand fragments read from LDS through a ring of kRing registers sets: the read of
+  // fragment i+kRing-1 is issued before the product with fragment i, so a product never waits
+  // for the read issued just before it.
+  constexpr int kRing = sizeof(T) == 2 ? 4 : 2;                 // fp32 fragments are twice as large
+  auto mfma_phase = [&](auto pv_c, auto ss_c, int tile) {
+    constexpr bool PV = decltype(pv_c)::value, SS = decltype(ss_c)::value;
+    constexpr int NPV = PV ? CB * NB : 0, NSS = SS ? NB * CB : 0, TOT = NPV + NSS;
+    const T* st = smem + (long)(tile & 1) * L::kStageElems;    // K(tile) and V(tile-1) share a stage
+    const T* kbase = st + lr * L::kKRowElems + 16 * h;
+    const T* vbase = st + L::kKElems + lr * L::kVRowElems + 16 * h;
+    auto fetch = [&](int i) -> Frag<T> {
+      if (i < NPV) return load_frag<T>(vbase + (i / NB) * 32 * L::kVRowElems + (i % NB) * 32);
+      const int j = i - NPV;
+      return load_frag<T>(kbase + (j / CB) * 32 * L::kKRowElems + (j % CB) * 32);
+    };
+    if (SS) {
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
+      for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) s[qb][nb][e] = 0.f;
+          for (int e = 0; e < 16; ++e) s[qb][nb][e] = 0.f;
+    }
+    Frag<T> ring[kRing];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int i = 0; i < kRing - 1 && i < TOT; ++i) ring[i] = fetch(i);
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) {
-        Frag<T> kf = load_frag<T>(ks + (nb * 32 + lr) * L::kKRowElems + cb * 32 + 16 * h);
+    for (int i = 0; i < TOT; ++i) {
+      if (i + kRing - 1 < TOT) ring[(i + kRing - 1) % kRing] = fetch(i + kRing - 1);
+      __builtin_amdgcn_sched_barrier(0);                        // keep the read ahead of the products
+      const Frag<T>& f = ring[i % kRing];
+      if (i < NPV) {
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) mma32(s[qb][nb], kf, qf[qb][cb]);
+        for (int qb = 0; qb < QB; ++qb) mma32(oacc[qb][i / NB], f, pf[qb][i % NB]);
+      } else {
+        const int j = i - NPV;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) mma32(s[qb][j / CB], f, qf[qb][j % CB]);
       }
-
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  constexpr std::true_type kYes{};
+  constexpr std::false_type kNo{};
+  auto do_softmax = [&](int tile) {                             // s of `tile` -> pf, running sums
+    const int n0 = tile * BC;
     // mask: keys beyond the sequence, and (causal) keys after the query
     const bool need_mask = (n0 + BC > p.N) || (p.causal && n0 + BC - 1 > t0);
     if (need_mask) {
@@ -229,9 +273,7 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
           }
       }
     }
-
     // online softmax (scores already carry log2(e)/sqrt(d_head))
-    Frag<T> pf[QB][NB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       float mx = -INFINITY;
@@ -260,19 +302,39 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
         l_run[qb] = frag_sum(pf[qb][nb], l_run[qb]);
       }
     }
+  };
 
-    // O^T += V^T P^T
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        Frag<T> vf = load_frag<T>(vs + (cb * 32 + lr) * L::kVRowElems + nb * 32 + 16 * h);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) mma32(oacc[qb][cb], vf, pf[qb][nb]);
-      }
-
-    if (tile + 1 < n_tiles) s_store(cur ^ 1);
+  s_store(0);                                                   // K(0); the V part of stage 0 is never read
+  __syncthreads();
+  const int last = n_tiles - 1;
+  if (wave < NT / 128) {                                        // ---- MFMA phase first
+    g_load(min(1, last), 0);
+    mfma_phase(kNo, kYes, 0);
+    do_softmax(0);
+    s_store(1);
     __syncthreads();
+    for (int t = 1; t < n_tiles; ++t) {
+      g_load(min(t + 1, last), t);
+      mfma_phase(kYes, kYes, t);
+      do_softmax(t);
+      s_store((t + 1) & 1);
+      __syncthreads();
+    }
+    mfma_phase(kYes, kNo, n_tiles);
+  } else {                                                      // ---- softmax phase first
+    g_load(min(1, last), 0);
+    mfma_phase(kNo, kYes, 0);
+    s_store(1);
+    __syncthreads();
+    for (int t = 1; t < n_tiles; ++t) {
+      g_load(min(t + 1, last), t);
+      do_softmax(t - 1);
+      mfma_phase(kYes, kYes, t);
+      s_store((t + 1) & 1);
+      __syncthreads();
+    }
+    do_softmax(last);
+    mfma_phase(kYes, kNo, n_tiles);
   }
 
   // ---- epilogue: normalise, store O[tok][head][c] (acc order in c) -------------------------

@@ -119,6 +119,32 @@ template <> __device__ __forceinline__ void store_frag<bf16>(bf16* p, const Frag
   q[1] = f.v[1];
 }
 
+// Fragment-major storage of an operand matrix: every 32 (rows) x 32 (contraction positions)
+// block is kept as 1024 consecutive elements ordered [16-byte chunk j][lane][element], so
+// that the j-th 16-byte load of all 64 lanes of a wave reads one contiguous kilobyte.
+// Lane = 32*h + row, where half h owns stored positions 16h .. 16h+15 of the block.
+constexpr int kFragBlockElems = 1024;
+template <typename T> __host__ __device__ constexpr int frag_major_offset(int row, int pos) {
+  constexpr int CE = 16 / (int)sizeof(T);
+  const int lane = 32 * (pos / 16) + row, p16 = pos % 16;
+  return ((p16 / CE) * 64 + lane) * CE + p16 % CE;
+}
+template <typename T> __device__ __forceinline__ Frag<T> load_frag_major(const T* block, int lane);
+template <> __device__ __forceinline__ Frag<float> load_frag_major<float>(const float* block, int lane) {
+  Frag<float> f;
+  const f32x4* q = reinterpret_cast<const f32x4*>(block) + lane;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) f.v[i] = q[64 * i];
+  return f;
+}
+template <> __device__ __forceinline__ Frag<bf16> load_frag_major<bf16>(const bf16* block, int lane) {
+  Frag<bf16> f;
+  const bf16x8* q = reinterpret_cast<const bf16x8*>(block) + lane;
+  f.v[0] = q[0];
+  f.v[1] = q[64];
+  return f;
+}
+
 // four consecutive accumulator registers (rows 8q+4h .. +3) -> 4 elements of T at p (natural order)
 __device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
   *reinterpret_cast<f32x4*>(p) = f32x4{a, b, c, d};

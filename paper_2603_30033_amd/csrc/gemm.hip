@@ -97,10 +97,10 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, in
       if (g.rope != nullptr) {
         // (cos, sin) of two adjacent pairs per load, all four loads issued before the first use;
         // rows of padding tokens hold zeros, so any table row serves them
-        const f32x4* tab = reinterpret_cast<const f32x4*>(g.rope + (long)(valid ? pos : 0) * (g.D / 2) + (c0 + 4 * h) / 2);
+        const f32x4* tab = reinterpret_cast<const f32x4*>(g.rope) + (long)(c0 / 4 + h) * g.rope_ld + (valid ? pos : 0);
         f32x4 cs[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) cs[q] = tab[2 * q];
+        for (int q = 0; q < 4; ++q) cs[q] = tab[(long)2 * q * g.rope_ld];
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll

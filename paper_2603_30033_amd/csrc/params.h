@@ -11,7 +11,8 @@ namespace ta {
 // out[z][u][v] = scale * sum_a coef[z][a] * src[a][row][col]   with (u,v) = (col,row) when
 // transposed, (row,col) otherwise; rows/cols beyond the source extents read as zero so the
 // padded part of the output is written as zero.  perm: store column v of each 32-block at
-// its acc-order position.
+// its acc-order position.  frag: the output is fragment-major (see common.h): 32x32 blocks of
+// (u, v), block (u/32, v/32) at ((u/32) * n_vblocks + v/32) * 1024 from out + z*out_stride_z.
 struct PrepJob {
   const void* src;      // [A][rows][cols]
   const void* coef;     // [Z][A] or null (A must be 1, coefficient 1)
@@ -20,7 +21,7 @@ struct PrepJob {
   int Z;
   int rows_pad, cols_pad;   // padded extents covered by tiles (multiples of 32)
   long out_stride_z, out_stride_u;
-  int transposed, perm;
+  int transposed, perm, frag;
   float scale;
   int first_block;      // prefix sum of tile counts
 };
@@ -50,7 +51,11 @@ struct GemmArgs {
   void* Vt;                     // [B][D][Npad], n in acc order within 32-blocks; null in decode
   void* Kcache; void* Vcache;   // nullable [B][Lmax][r3]/[B][Lmax][rt3], natural order
   int Lmax, r3, rt3;
-  const float2* rope;           // [max_pos][D/2] (cos, sin), identity beyond r3/2, or null
+  // rotation table or null: [D/4][rope_ld positions] entries (cos, sin, cos, sin) of the channel
+  // pairs (4k, 4k+1), (4k+2, 4k+3); identity beyond r3.  Positions are the fast index, so lanes
+  // that hold consecutive tokens read consecutive entries.
+  const float4* rope;
+  int rope_ld;
   int pos0;
   int decode;                   // 1: one token per sequence, position/cache row from kv_pos[b]
   int kv_pos[32];
@@ -70,7 +75,8 @@ struct AttnArgs {
   const void* Kr;     // [TP][D]
   const void* Vt;     // [B][D][Npad]
   void* O;            // [TP][nH][D] acc order in c, normalised
-  const float2* rope; // or null
+  const float4* rope; // [D/4][rope_ld] as in GemmArgs, or null
+  int rope_ld;
   int Bsz, N, Npad, nH, R2, r3, D;   // D = padded common width of K and V (32, 64 or 128)
   int causal, pos0;
 };
@@ -86,7 +92,8 @@ struct DecodeArgs {
   float* part_l;
   float* part_o;       // [B][nsplit][HB*32][D]
   void* O;             // [32][nH][D] acc order in c (rows >= B zero)
-  const float2* rope;
+  const float4* rope; // [D/4][rope_ld] as in GemmArgs, or null
+  int rope_ld;
   int Bsz, nH, HB, R2, r3, rt3, D, Lmax, nsplit;
   int kv_len[32];
 };

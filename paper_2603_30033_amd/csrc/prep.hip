@@ -50,7 +50,14 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs args) {
     } else {
       u = r0 + a; v = c0 + vpos; val = tile[a][tx];
     }
-    store1(out + (long)z * jb.out_stride_z + u * jb.out_stride_u + v, val);
+    long off;
+    if (jb.frag) {
+      const int nvb = (jb.transposed ? jb.rows_pad : jb.cols_pad) / 32;
+      off = ((u / 32) * nvb + v / 32) * kFragBlockElems + frag_major_offset<T>((int)(u % 32), (int)(v % 32));
+    } else {
+      off = u * jb.out_stride_u + v;
+    }
+    store1(out + (long)z * jb.out_stride_z + off, val);
   }
 }
 
