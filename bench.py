@@ -22,6 +22,14 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel (read + written), from the rocprofv3 FETCH_SIZE and
+# WRITE_SIZE runs summarised in profiles/hbm_traffic_<workload>.md, scaled by what the same counters
+# read for a plain 256 MiB copy (factors 1.9998 and 1.0000).  Workloads without a counter run report null.
+MEASURED_TRAFFIC_BYTES = {
+    ("llama7b_n4096", "attention"): 183925942,
+    ("decode_32k", "decode_attention"): 278085020,
+}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -192,13 +200,15 @@ def main():
         alg_bytes = w.B * w.kv_len * (w.r3 + rt3) * es
         ach = alg_bytes / (kern_ms[dom] * 1e-3) / 1e9
         roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_us": kern_ms[dom] * 1e3}
+                "frac": ach / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                "algorithmic_bytes": alg_bytes, "avg_us": kern_ms[dom] * 1e3}
     else:
         dom = "attention"
         peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS
         ach = (fl["attn"] + fl["qhat"]) / (kern_ms[dom] * 1e-3) / 1e12
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                "frac": ach / peak, "traffic": None, "avg_us": kern_ms[dom] * 1e3}
+                "frac": ach / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                "algorithmic_flops": fl["attn"] + fl["qhat"], "avg_us": kern_ms[dom] * 1e3}
 
     out = {
         "metric": "tucker_attn_fwd_tflops" if w.mode != "decode" else "tucker_attn_decode_tflops",
