@@ -259,16 +259,35 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs p) {
   const int head = (idx / p.D) % p.nH;
   const int b = idx / ((long)p.D * p.nH);
   const int HB32 = p.HB * 32;
-  float mmax = -INFINITY;
-  for (int s = 0; s < p.nsplit; ++s) mmax = fmaxf(mmax, p.part_m[((long)b * p.nsplit + s) * HB32 + head]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < p.nsplit; ++s) {
-    const long ps = ((long)b * p.nsplit + s) * HB32 + head;
-    const float mval = p.part_m[ps];
-    if (mval == -INFINITY) continue;                              // empty split
-    const float w = fast_exp2(mval - mmax);
-    den += w * p.part_l[ps];
-    num += w * p.part_o[ps * p.D + c];
+  // one pass over the splits in batches of 8 whose loads are all issued before the first use;
+  // the running maximum is carried as in the attention kernel itself
+  constexpr int U = 8;
+  float mrun = -INFINITY, num = 0.f, den = 0.f;
+  for (int s0 = 0; s0 < p.nsplit; s0 += U) {
+    float mv[U], lv[U], ov[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long ps = ((long)b * p.nsplit + min(s0 + u, p.nsplit - 1)) * HB32 + head;
+      mv[u] = p.part_m[ps];
+      lv[u] = p.part_l[ps];
+      ov[u] = p.part_o[ps * p.D + c];
+    }
+    float mb = mrun;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (s0 + u < p.nsplit) mb = fmaxf(mb, mv[u]);
+    if (mb == -INFINITY) continue;                                // only empty splits so far
+    const float a = fast_exp2(mrun - mb);                         // 0 while mrun is still -inf
+    num *= a;
+    den *= a;
+    mrun = mb;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool live = s0 + u < p.nsplit && mv[u] != -INFINITY;  // beyond the end, or an empty split
+      const float w = live ? fast_exp2(mv[u] - mb) : 0.f;
+      den += w * lv[u];
+      num += w * ov[u];
+    }
   }
   T* O = static_cast<T*>(p.O);
   store1(O + ((long)b * p.nH + head) * p.D + (c & ~31) + acc_pos(c & 31), num / den);

@@ -26,17 +26,42 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs args) {
   const T* coef = static_cast<const T*>(jb.coef);
   T* out = static_cast<T*>(jb.out);
 
+  // all loads of a batch of up to 8 core slices x 4 rows are issued before the first use, so a
+  // workgroup pays for one round trip to memory per batch rather than one per slice
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  const int col = c0 + tx;
+  if (jb.A == 1) {                                              // plain (transposed) copy of one matrix
+    const float w = coef ? to_f32(coef[z]) : 1.f;
 #pragma unroll
-  for (int rr = 0; rr < 4; ++rr) {
-    int row = r0 + ty + 8 * rr, col = c0 + tx;
-    float acc = 0.f;
-    if (row < jb.rows && col < jb.cols) {
-      for (int a = 0; a < jb.A; ++a) {
-        float cf = coef ? to_f32(coef[(long)z * jb.A + a]) : 1.f;
-        acc += cf * to_f32(src[((long)a * jb.rows + row) * jb.cols + col]);
+    for (int rr = 0; rr < 4; ++rr) {
+      const int row = min(r0 + ty + 8 * rr, jb.rows - 1);
+      acc[rr] = w * to_f32(src[(long)row * jb.cols + min(col, jb.cols - 1)]);
+    }
+  } else
+  for (int a0 = 0; a0 < jb.A; a0 += 8) {
+    T v[8][4];
+    T cf[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int a = min(a0 + k, jb.A - 1);                      // clamped: slices past the end get weight 0
+      cf[k] = coef ? coef[(long)z * jb.A + a] : (T)1.f;
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int row = min(r0 + ty + 8 * rr, jb.rows - 1);
+        v[k][rr] = src[((long)a * jb.rows + row) * jb.cols + min(col, jb.cols - 1)];
       }
     }
-    tile[ty + 8 * rr][tx] = acc * jb.scale;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float w = a0 + k < jb.A ? to_f32(cf[k]) : 0.f;
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) acc[rr] += w * to_f32(v[k][rr]);
+    }
+  }
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    const bool inside = r0 + ty + 8 * rr < jb.rows && col < jb.cols;
+    tile[ty + 8 * rr][tx] = inside ? acc[rr] * jb.scale : 0.f;
   }
   __syncthreads();
   int vpos = jb.perm ? acc_pos(tx) : tx;
