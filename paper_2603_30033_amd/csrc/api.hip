@@ -323,7 +323,9 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
   y.Bsrc = ws.Z; y.ldb = c->RT2; y.K = c->RT2;
   y.Bsz = B; y.N = N; y.Npad = Npad; y.src_padded = 1;
   y.epi = 2; y.Out = Y; y.ldo = f.d_model; y.ksplit = 1;
-  if (launch_gemm(f.dtype, y, pick_tile_n((y.M + 127) / 128, TP, y.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  const hipError_t ye = out_proj_supported(f.dtype, y) ? launch_out_proj(f.dtype, y, s)
+                                                       : launch_gemm(f.dtype, y, pick_tile_n((y.M + 127) / 128, TP, y.K), s);
+  if (ye != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
   rec.after("output_projection");
   return TUCKER_ATTN_OK;
 }

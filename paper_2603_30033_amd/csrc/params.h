@@ -71,7 +71,7 @@ struct GemmArgs {
 // ---- prefill attention ---------------------------------------------------------------------
 struct AttnArgs {
   const void* Qlat;   // [TP][R2] acc order
-  const void* Gt;     // [nH][D][R2]  Gt[i][c][b] = qscale * G_i[b][c], b in acc order
+  const void* Gt;     // [nH] x fragment-major 32x32 blocks of Gt[i][c][b] = qscale * G_i[b][c], b in acc order
   const void* Kr;     // [TP][D]
   const void* Vt;     // [B][D][Npad]
   void* O;            // [TP][nH][D] acc order in c, normalised
@@ -99,6 +99,8 @@ struct DecodeArgs {
 };
 
 hipError_t launch_prep(int dtype, const PrepArgs& a, hipStream_t s);
+bool out_proj_supported(int dtype, const GemmArgs& a);
+hipError_t launch_out_proj(int dtype, const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm(int dtype, const GemmArgs& a, int tile_n, hipStream_t s);
 hipError_t launch_attn_prefill(int dtype, const AttnArgs& a, hipStream_t s);
 hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, hipStream_t s);
