@@ -116,42 +116,47 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeArgs p) {
     for (int e = 0; e < 16; ++e) oacc[hb][e] = 0.f;
   }
 
+  // Cache rows travel global -> registers -> LDS.  Two register sets alternate, each filled two
+  // tiles ahead of its use by buffer loads whose range check supplies the zeros (rows past
+  // kv_len, channels past r3 / rt3, tiles past this split), so no load sits behind a branch and
+  // two tiles per workgroup are always in flight.
   const T* Kc = static_cast<const T*>(p.Kcache) + (long)b * p.Lmax * p.r3;
   const T* Vc = static_cast<const T*>(p.Vcache) + (long)b * p.Lmax * p.rt3;
-  u32x4 kreg[PT], vreg[PT];
-  auto g_load = [&](int tile) {
-    const int n0 = tile * BC;
+  const long lim = 0x7fffffffl;
+  const long kbytes = (long)Lb * p.r3 * (long)sizeof(T), vbytes = (long)Lb * p.rt3 * (long)sizeof(T);
+  __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(Kc), 0, (int)(kbytes > lim ? lim : kbytes), 0x00020000);
+  __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(Vc), 0, (int)(vbytes > lim ? lim : vbytes), 0x00020000);
+  struct Set { u32x4 k[PT], v[PT]; } ra, rb;
+  int srow[PT], scol[PT];
+#pragma unroll
+  for (int i = 0; i < PT; ++i) {
+    const int ci = threadIdx.x + i * 256;
+    srow[i] = ci / CPR;
+    scol[i] = (ci % CPR) * CE;
+  }
+  auto g_load = [&](Set& r, int tile) {
+    const bool live = tile < t_last;
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
-      int ci = threadIdx.x + i * 256;
-      int row = ci / CPR, col = (ci % CPR) * CE;
-      int n = n0 + row;
-      u32x4 z = {0u, 0u, 0u, 0u};
-      kreg[i] = (n < Lb && col < p.r3) ? *reinterpret_cast<const u32x4*>(Kc + (long)n * p.r3 + col) : z;
-      vreg[i] = (n < Lb && col < p.rt3) ? *reinterpret_cast<const u32x4*>(Vc + (long)n * p.rt3 + col) : z;
+      const long n = (long)tile * BC + srow[i];
+      const uint32_t ko = (live && scol[i] < p.r3) ? (uint32_t)((n * p.r3 + scol[i]) * (long)sizeof(T)) : 0x80000000u;
+      const uint32_t vo = (live && scol[i] < p.rt3) ? (uint32_t)((n * p.rt3 + scol[i]) * (long)sizeof(T)) : 0x80000000u;
+      r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, ko, 0, 0);
+      r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, vo, 0, 0);
     }
   };
-  auto s_store = [&](int stage) {
+  auto s_store = [&](const Set& r, int stage) {
     T* ks = smem + (long)stage * L::kStageElems;
     T* vs = ks + L::kTileElems;
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
-      int ci = threadIdx.x + i * 256;
-      int row = ci / CPR, col = (ci % CPR) * CE;
-      *reinterpret_cast<u32x4*>(ks + row * L::kRowElems + col) = kreg[i];
-      *reinterpret_cast<u32x4*>(vs + row * L::kRowElems + col) = vreg[i];
+      *reinterpret_cast<u32x4*>(ks + srow[i] * L::kRowElems + scol[i]) = r.k[i];
+      *reinterpret_cast<u32x4*>(vs + srow[i] * L::kRowElems + scol[i]) = r.v[i];
     }
   };
 
-  if (t_first < t_last) {
-    g_load(t_first);
-    s_store(0);
-  }
-  __syncthreads();
-
-  for (int tile = t_first; tile < t_last; ++tile) {
-    const int cur = (tile - t_first) & 1;
-    if (tile + 1 < t_last) g_load(tile + 1);
+  // one tile from LDS stage `cur`
+  auto compute = [&](int tile, int cur) {
     const T* ks = smem + (long)cur * L::kStageElems;
     const T* vs = ks + L::kTileElems;
     const int n0 = tile * BC;
@@ -226,7 +231,31 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeArgs p) {
         for (int hb = 0; hb < HB; ++hb) mma32(oacc[hb], vf, pf[hb][nb]);
       }
     }
-    if (tile + 1 < t_last) s_store(cur ^ 1);
+  };
+
+  // The slices of different workgroups lie a power of two apart in memory; walking them in step
+  // would keep all workgroups on the same memory channels.  Each workgroup therefore starts at
+  // its own tile of its slice and wraps around (the online softmax does not care about order).
+  const int cnt = max(t_last - t_first, 0);
+  const int rot = cnt > 0 ? (int)((split * 5u + b * 3u) % (unsigned)cnt) : 0;
+  auto tile_at = [&](int j) {                                     // j-th tile in this workgroup's order
+    int r = j + rot;
+    if (r >= cnt) r -= cnt;
+    return j < cnt ? t_first + r : t_last;                        // past the end: a dead tile
+  };
+  g_load(ra, tile_at(0));
+  g_load(rb, tile_at(1));
+  s_store(ra, 0);
+  g_load(ra, tile_at(2));
+  __syncthreads();
+  for (int j = 0; j < cnt; j += 2) {
+    compute(tile_at(j), 0);
+    s_store(rb, 1);
+    g_load(rb, tile_at(j + 3));
+    __syncthreads();
+    if (j + 1 < cnt) compute(tile_at(j + 1), 1);
+    s_store(ra, 0);
+    g_load(ra, tile_at(j + 4));
     __syncthreads();
   }
 
