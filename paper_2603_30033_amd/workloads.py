@@ -7,9 +7,10 @@ sees a value produced by the other.
 
 Shapes follow the paper's problem statement (Definition "Tucker Attention":
 core C[r1,r2,r3], U1[nH,r1], U2[d,r2], U3[d,r3] and the tilde set for the
-post-softmax tensor); the five named workloads take the model shapes of the
+post-softmax tensor); the first five named workloads take the model shapes of the
 paper's hyper-parameter table (GPT-2 small, ViT-B/16) and an N=4096 LLaMA-like
-layer.  The paper's datasets are not used: attention-forward cost does not
+layer; two more take rank shapes the paper itself trains ([8,128,64] on GPT-2,
+[32,128,128] on its LLaMA3-1B layer).  The paper's datasets are not used: attention-forward cost does not
 depend on the data, so Gaussian tokens stand in for them.
 
 Value recipes
@@ -80,6 +81,14 @@ WORKLOADS: Dict[str, Workload] = {
     "decode_32k": Workload("decode_32k", B=16, N=1, d_model=4096, n_heads=32, d_head=128,
                            r1=8, r2=128, r3=128, dtype="bf16", causal=True, rope_base=1e4,
                            seed=4, recipe="orthonormal", mode="decode", kv_len=32768),
+    # the paper's own rank shapes (tables of Section "Experiments"): unequal query and key ranks on
+    # the GPT-2 layer, and its LLaMA3-1B layer with r1 = nH and RoPE base 5e5
+    "gpt2_r8_128_64": Workload("gpt2_r8_128_64", B=8, N=1024, d_model=768, n_heads=12, d_head=64,
+                               r1=8, r2=128, r3=64, dtype="bf16", causal=True, rope_base=1e4,
+                               seed=5, recipe="orthonormal", layernorm_x=True),
+    "llama1b_r32_128_128": Workload("llama1b_r32_128_128", B=4, N=2048, d_model=2048, n_heads=32, d_head=64,
+                                    r1=32, r2=128, r3=128, dtype="bf16", causal=True, rope_base=5e5,
+                                    seed=6, recipe="orthonormal"),
 }
 
 

@@ -88,6 +88,30 @@ def test_config4_llama_scaled_full_and_full_size_sampled():
     check(y[:, rows], ref, base.dtype, "llama full")
 
 
+def test_paper_rank_shape_gpt2_8_128_64_scaled_full_and_full_size_sampled():
+    base = wl.WORKLOADS["gpt2_r8_128_64"]                  # r2 != r3: query rank 128, key/value rank 64
+    w = wl.scaled(base, B=2, N=300)
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), w.dtype, "gpt2 [8,128,64] B=2 N=300")
+    inp = wl.make_inputs(base)
+    rows = [0, 1, 63, 64, 65, 511, 512, 1000, 1023]
+    y = run_forward(base, inp)
+    ref = oracle_forward(base, inp, rows=rows, batches=[0, 7])
+    check(y[[0, 7]][:, rows], ref, base.dtype, "gpt2 [8,128,64] full")
+
+
+def test_paper_rank_shape_llama1b_32_128_128_scaled_full_and_full_size_sampled():
+    base = wl.WORKLOADS["llama1b_r32_128_128"]             # r1 = nH, RoPE base 5e5
+    w = wl.scaled(base, B=1, N=320)
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), w.dtype, "llama1b B=1 N=320")
+    inp = wl.make_inputs(base)
+    rows = [0, 1, 64, 1023, 1024, 2046, 2047]
+    y = run_forward(base, inp)
+    ref = oracle_forward(base, inp, rows=rows, batches=[0, 3])
+    check(y[[0, 3]][:, rows], ref, base.dtype, "llama1b full")
+
+
 def run_decode(w, inp):
     with Layer(w, inp, max_positions=int(max(inp["kv_len"])) + 1) as layer:
         x = to_device(inp["X"][:, 0], w.dtype)
