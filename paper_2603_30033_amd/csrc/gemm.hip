@@ -422,6 +422,10 @@ hipError_t launch_gemm(int dtype, const GemmArgs& a, int tile_n, hipStream_t s) 
     if (tile_n >= 64) return launch_one<float, 128, 64, 2, 2>(a, m_rows, s);
     return launch_one<float, 128, 32, 4, 1>(a, m_rows, s);
   }
+  // 129..192 weight rows (three 64-wide factor blocks): one 192-row tile instead of one full and one
+  // half-empty 128-row tile, and the token rows are read once (only when the token tiles alone give every compute unit two workgroups)
+  if (tile_n == 64 && m_rows > 128 && m_rows <= 192 && ((long)a.Bsz * a.Npad + 63) / 64 >= 512)
+    return launch_one<bf16, 192, 64, 2, 2>(a, m_rows, s);
   if (tile_n >= 128) return launch_one<bf16, 128, 128, 2, 2>(a, m_rows, s);
   if (tile_n >= 64) return launch_one<bf16, 128, 64, 2, 2>(a, m_rows, s);
   return launch_one<bf16, 128, 32, 4, 1>(a, m_rows, s);
