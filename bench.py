@@ -49,7 +49,7 @@ def flops(w, N=None, B=None):
     else:
         T = B * N
         pairs = N * (N + 1) // 2 if w.causal else N * N
-    proj = 2 * T * d * (w.r2 + w.r3 + rt3)
+    proj = 2 * T * d * (w.r2 + w.r3 + (0 if w.shared_kv else rt3))      # a shared latent is projected once
     qhat = min(2 * T * nH * w.r2 * w.r3, 2 * T * w.r1 * w.r2 * w.r3 + 2 * T * nH * w.r1 * w.r3)
     attn = B * nH * pairs * (2 * w.r3 + 2 * rt3)
     merge = min(2 * T * nH * rt2 * rt3, 2 * T * rt1 * rt2 * rt3 + 2 * T * nH * rt1 * rt3)
@@ -64,7 +64,7 @@ def mandatory_bytes(w):
     wts = (w.r1 * w.r2 * w.r3 + rt1 * rt2 * rt3 + w.n_heads * (w.r1 + rt1)
            + w.d_model * (w.r2 + w.r3 + rt2 + rt3)) * es
     if w.mode == "decode":
-        return w.B * w.kv_len * (w.r3 + rt3) * es + wts + 2 * w.B * w.d_model * es
+        return w.B * w.kv_len * (w.r3 + (0 if w.shared_kv else rt3)) * es + wts + 2 * w.B * w.d_model * es
     return 2 * w.B * w.N * w.d_model * es + wts
 
 
@@ -79,8 +79,12 @@ def cpu_baseline(w):
         ws = wl.scaled(w, B=2)
         inp = wl.make_inputs(ws)
         t0 = time.perf_counter()
-        orc.decode_step(inp["X"][:, 0], inp["Kcache"], inp["Vcache"], inp["kv_len"], wl.weights_of(inp),
-                        ws.d_head, ws.rope_base)
+        if ws.shared_kv:
+            orc.decode_step_shared_kv(inp["X"][:, 0], inp["Lcache"], inp["kv_len"], wl.weights_of(inp),
+                                      ws.d_head, ws.rope_base)
+        else:
+            orc.decode_step(inp["X"][:, 0], inp["Kcache"], inp["Vcache"], inp["kv_len"], wl.weights_of(inp),
+                            ws.d_head, ws.rope_base)
         dt = time.perf_counter() - t0
         f = flops(ws)["total"]
         sample = f"decode step of {ws.B} of the {w.B} sequences at kv_len={w.kv_len} (cache given, as for the GPU)"
@@ -144,7 +148,10 @@ def main():
             y = torch.empty_like(x)
             # three cache copies in rotation so that a step streams its cache from HBM, not from
             # the last-level cache that the previous step filled
-            caches = [(to_device(inp["Kcache"], w.dtype), to_device(inp["Vcache"], w.dtype)) for _ in range(3)]
+            if w.shared_kv:
+                caches = [(to_device(inp["Lcache"], w.dtype), None) for _ in range(3)]
+            else:
+                caches = [(to_device(inp["Kcache"], w.dtype), to_device(inp["Vcache"], w.dtype)) for _ in range(3)]
             lens = [int(v) for v in inp["kv_len"]]
             ws = layer.workspace(ta.tucker_attn_decode_workspace_bytes(layer.ctx, w.B))
             step_i = [0]
@@ -197,7 +204,7 @@ def main():
         dom = "decode_attention"
         es = 2 if w.dtype == "bf16" else 4
         rt3 = w.ranks_post()[2]
-        alg_bytes = w.B * w.kv_len * (w.r3 + rt3) * es
+        alg_bytes = w.B * w.kv_len * (w.r3 + (0 if w.shared_kv else rt3)) * es
         ach = alg_bytes / (kern_ms[dom] * 1e-3) / 1e9
         roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": ach / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
@@ -216,7 +223,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "N": w.N if w.mode != "decode" else w.kv_len,
                    "d_model": w.d_model, "n_heads": w.n_heads, "d_head": w.d_head,
-                   "ranks": [w.r1, w.r2, w.r3], "causal": w.causal, "rope_base": w.rope_base, "mode": w.mode},
+                   "ranks": [w.r1, w.r2, w.r3], "causal": w.causal, "rope_base": w.rope_base, "mode": w.mode,
+                   "shared_kv": w.shared_kv},
         "tokens_per_s": units / (ms * 1e-3),
         "pct_mfma_peak": 100.0 * tflops / (PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS),
         "hbm_gbs_mandatory": mandatory_bytes(w) / (ms * 1e-3) / 1e9,

@@ -68,6 +68,11 @@ typedef struct {
   int32_t dtype;          /* TUCKER_ATTN_F32 | TUCKER_ATTN_BF16: storage of X, weights, caches, Y; */
                           /* products accumulate in fp32 in both cases                             */
   int32_t max_positions;  /* rotation table covers positions 0 .. max_positions-1 (>= pos0+N, Lmax)*/
+  int32_t shared_kv;      /* 0 | 1: shared key-value down-projection (Section "KV Caching"): the  */
+                          /* value basis IS the key basis U3, so V = X U3 is the unrotated key     */
+                          /* latent; needs rt3 == r3; weights.Ut3 is ignored (may be NULL); ONE    */
+                          /* cache [B, Lmax, r3] holds the UNROTATED latent and keys are rotated   */
+                          /* when a cache tile is read                                             */
 } tucker_attn_config;
 
 /* Device pointers to the weights; read-only, caller-owned. */
@@ -84,8 +89,8 @@ typedef struct {
 
 /*
  * Create a context (Definition "Tucker Attention" fixes the shapes).  Host work plus one
- * device allocation (rotation table, max_positions * r3/2 cos/sin pairs in fp32, built in
- * double precision).  Limits of this build, reported as TUCKER_ATTN_UNSUPPORTED_SHAPE:
+ * device allocation (rotation table: for every position below max_positions the cos/sin pairs
+ * of the r3/2 channel pairs, padded to a multiple of 16 pairs, fp32, built in double precision).  Limits of this build, reported as TUCKER_ATTN_UNSUPPORTED_SHAPE:
  * r3, rt3 <= 128; r2, rt2 <= 512; r1, rt1 <= 64; d_model a multiple of 8; r3 even when
  * use_rope; ranks need not be multiples of 32 (they are zero-padded internally).
  */
@@ -109,7 +114,8 @@ size_t tucker_attn_decode_workspace_bytes(const tucker_attn_ctx *ctx, int32_t B)
  *   Y            device [B, N, d]      out
  *   Kcache_out   device [B, Lmax, r3]  out, nullable: rows pos0..pos0+N-1 receive the rotated keys
  *   Vcache_out   device [B, Lmax, rt3] out, nullable: same rows receive the values
- *                (both or neither; needs pos0+N <= Lmax)
+ *                (both or neither; needs pos0+N <= Lmax).  With shared_kv: Vcache_out must be
+ *                NULL and Kcache_out, if given, receives the UNROTATED latent rows.
  *   workspace    device, >= tucker_attn_workspace_bytes(ctx,B,N) bytes, 256-byte aligned; scratch
  *   hip_stream   a hipStream_t (NULL = the null stream)
  */
@@ -124,6 +130,8 @@ int tucker_attn_forward(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
  *   y        device [B, d]            out
  *   Kcache   device [B, Lmax, r3]     in/out: row kv_len[b]-1 is written (rotated key of x[b])
  *   Vcache   device [B, Lmax, rt3]    in/out: row kv_len[b]-1 is written (value of x[b])
+ *            With shared_kv: Vcache must be NULL and Kcache is the one cache of unrotated latent
+ *            rows (row kv_len[b]-1 is written unrotated).
  *   kv_len   HOST   [B] int32         cache length INCLUDING the new token, 1 <= kv_len[b] <= Lmax;
  *                                     the query sits at position kv_len[b]-1 and attends rows 0..kv_len[b]-1
  *   B        1 .. 32

@@ -266,6 +266,38 @@ def decode_step(x, Kcache, Vcache, kv_len, wts: Dict[str, np.ndarray], d_head: i
     return y, Kc, Vc
 
 
+def decode_step_shared_kv(x, Lcache, kv_len, wts: Dict[str, np.ndarray], d_head: int,
+                          rope_base: Optional[float] = None):
+    """Decode with the shared key-value down-projection of Section "KV Caching": keys and values
+    are both the latent L = X U3, so ONE cache of N*r3 numbers is kept.  Because latent RoPE
+    rotates keys but never values, the cache holds the UNROTATED latent; the key of row n is its
+    rotation to position n, formed when the row is read.  The value basis of wts is not used.
+
+    x [B,d]; Lcache [B,Lmax,r3]; kv_len[b] includes the new token, whose latent is written to
+    row kv_len[b]-1.  Returns (y [B,d], Lcache_new) as fp64 copies.
+    """
+    x = _f64(x)
+    Lc = _f64(Lcache).copy()
+    WQ, WK, _, WO = per_head_weights(wts)
+    nH = WQ.shape[0]
+    B, d = x.shape
+    scale = 1.0 / math.sqrt(d_head)
+    y = np.zeros((B, d), dtype=F64)
+    for b in range(B):
+        L = int(kv_len[b])
+        Lc[b, L - 1] = (x[b:b + 1] @ WK)[0]
+        V = Lc[b, :L]
+        K = V if rope_base is None else rope_rotate(V, np.arange(L), rope_base)
+        p = np.array([L - 1])
+        for i in range(nH):
+            q = x[b:b + 1] @ WQ[i]
+            if rope_base is not None:
+                q = rope_rotate(q, p, rope_base)
+            P = softmax_rows((q @ K.T) * scale)
+            y[b] += ((P @ V) @ WO[i])[0]
+    return y, Lc
+
+
 def relative_l2(a, b) -> float:
     """||a - b||_2 / ||b||_2 over all elements (b is the reference)."""
     a, b = _f64(a), _f64(b)

@@ -32,7 +32,7 @@ class tucker_attn_config(C.Structure):
                 ("r1", C.c_int32), ("r2", C.c_int32), ("r3", C.c_int32),
                 ("rt1", C.c_int32), ("rt2", C.c_int32), ("rt3", C.c_int32),
                 ("causal", C.c_int32), ("use_rope", C.c_int32), ("rope_base", C.c_float),
-                ("dtype", C.c_int32), ("max_positions", C.c_int32)]
+                ("dtype", C.c_int32), ("max_positions", C.c_int32), ("shared_kv", C.c_int32)]
 
 
 class tucker_attn_weights(C.Structure):
@@ -99,11 +99,12 @@ def _stream_ptr(stream) -> Optional[int]:
 
 
 def tucker_attn_create(*, d_model, n_heads, d_head, r1, r2, r3, rt1=None, rt2=None, rt3=None, causal=True,
-                       rope_base=None, dtype="bf16", max_positions=1) -> int:
+                       rope_base=None, dtype="bf16", max_positions=1, shared_kv=False) -> int:
     """Returns an opaque context handle (int).  Needs a current HIP device when rope_base is set."""
     cfg = tucker_attn_config(d_model, n_heads, d_head, r1, r2, r3, rt1 or r1, rt2 or r2, rt3 or r3,
                              int(bool(causal)), int(rope_base is not None), float(rope_base or 0.0),
-                             {"f32": TUCKER_ATTN_F32, "bf16": TUCKER_ATTN_BF16}[dtype], int(max_positions))
+                             {"f32": TUCKER_ATTN_F32, "bf16": TUCKER_ATTN_BF16}[dtype], int(max_positions),
+                             int(bool(shared_kv)))
     ctx = C.c_void_p()
     _check(load_library().tucker_attn_create(C.byref(cfg), C.byref(ctx)), "tucker_attn_create")
     return ctx.value
@@ -122,7 +123,7 @@ def tucker_attn_decode_workspace_bytes(ctx: int, B: int) -> int:
 
 
 def _weights_struct(w: Dict[str, "object"]) -> tucker_attn_weights:
-    return tucker_attn_weights(*[w[k].data_ptr() for k in ("C", "U1", "U2", "U3", "Ct", "Ut1", "Ut2", "Ut3")])
+    return tucker_attn_weights(*[_ptr(w.get(k)) for k in ("C", "U1", "U2", "U3", "Ct", "Ut1", "Ut2", "Ut3")])
 
 
 def tucker_attn_forward(ctx: int, weights: Dict, X, Y, pos0: int = 0, Kcache_out=None, Vcache_out=None,
@@ -143,14 +144,15 @@ def tucker_attn_forward(ctx: int, weights: Dict, X, Y, pos0: int = 0, Kcache_out
 
 def tucker_attn_decode(ctx: int, weights: Dict, x, y, Kcache, Vcache, kv_len: List[int], workspace=None,
                        stream=None, check: bool = True) -> int:
-    """x, y: [B, d]; Kcache/Vcache: [B, Lmax, r3]/[B, Lmax, rt3] (updated in place);
+    """x, y: [B, d]; Kcache/Vcache: [B, Lmax, r3]/[B, Lmax, rt3] (updated in place; with a shared
+    key-value projection Vcache is None and Kcache is the one cache of unrotated latent rows);
     kv_len: host ints, cache length including the new token."""
     B = int(x.shape[0])
     Lmax = int(Kcache.shape[1])
     lens = (C.c_int32 * B)(*[int(v) for v in kv_len])
     ws = _weights_struct(weights)
     st = load_library().tucker_attn_decode(ctx, C.byref(ws), x.data_ptr(), y.data_ptr(), Kcache.data_ptr(),
-                                           Vcache.data_ptr(), Lmax, lens, B,
+                                           _ptr(Vcache), Lmax, lens, B,
                                            _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                            _stream_ptr(stream))
     if check:

@@ -138,8 +138,9 @@ PrepArgs make_prep(const tucker_attn_ctx* c, const tucker_attn_weights* w, void*
   char* wc = static_cast<char*>(Wcat);
   add_job(pa, w->U2, nullptr, wc, 1, f.d_model, f.r2, 1, c->dp, c->R2, 0, c->dp, 1, 0, 1.f);
   add_job(pa, w->U3, nullptr, wc + (size_t)c->R2 * c->dp * es, 1, f.d_model, f.r3, 1, c->dp, c->D, 0, c->dp, 1, 0, 1.f);
-  add_job(pa, w->Ut3, nullptr, wc + (size_t)(c->R2 + c->D) * c->dp * es, 1, f.d_model, f.rt3, 1, c->dp, c->D, 0,
-          c->dp, 1, 0, 1.f);
+  if (!f.shared_kv)
+    add_job(pa, w->Ut3, nullptr, wc + (size_t)(c->R2 + c->D) * c->dp * es, 1, f.d_model, f.rt3, 1, c->dp, c->D, 0,
+            c->dp, 1, 0, 1.f);
   if (f.rt2 != c->RT2) {
     add_job(pa, w->Ut2, nullptr, Ut2p, 1, f.d_model, f.rt2, 1, c->dp, c->RT2, 0, c->RT2, 0, 0, 1.f);
     *ut2_used = Ut2p;
@@ -177,8 +178,8 @@ struct Recorder {
   }
 };
 
-bool weights_ok(const tucker_attn_weights* w) {
-  return w && w->C && w->U1 && w->U2 && w->U3 && w->Ct && w->Ut1 && w->Ut2 && w->Ut3;
+bool weights_ok(const tucker_attn_ctx* c, const tucker_attn_weights* w) {
+  return c && w && w->C && w->U1 && w->U2 && w->U3 && w->Ct && w->Ut1 && w->Ut2 && (w->Ut3 || c->cfg.shared_kv);
 }
 
 }  // namespace
@@ -194,6 +195,8 @@ int tucker_attn_create(const tucker_attn_config* cfg, tucker_attn_ctx** out) {
     return TUCKER_ATTN_INVALID_ARG;
   if (f.dtype != TUCKER_ATTN_F32 && f.dtype != TUCKER_ATTN_BF16) return TUCKER_ATTN_INVALID_ARG;
   if ((f.causal != 0 && f.causal != 1) || (f.use_rope != 0 && f.use_rope != 1)) return TUCKER_ATTN_INVALID_ARG;
+  if (f.shared_kv != 0 && f.shared_kv != 1) return TUCKER_ATTN_INVALID_ARG;
+  if (f.shared_kv && f.rt3 != f.r3) return TUCKER_ATTN_INVALID_ARG;
   if (f.use_rope && !(f.rope_base > 0.f)) return TUCKER_ATTN_INVALID_ARG;
   if (f.r3 > 128 || f.rt3 > 128 || f.r2 > 512 || f.rt2 > 512 || f.r1 > 64 || f.rt1 > 64)
     return TUCKER_ATTN_UNSUPPORTED_SHAPE;
@@ -265,10 +268,11 @@ size_t tucker_attn_decode_workspace_bytes(const tucker_attn_ctx* c, int32_t B) {
 int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* X, void* Y, int32_t B,
                         int32_t N, int32_t pos0, void* Kcache_out, void* Vcache_out, int32_t Lmax, void* workspace,
                         size_t workspace_bytes, void* hip_stream) {
-  if (!c || !weights_ok(w) || !X || !Y || !workspace) return TUCKER_ATTN_INVALID_ARG;
+  if (!c || !weights_ok(c, w) || !X || !Y || !workspace) return TUCKER_ATTN_INVALID_ARG;
   if (B < 1 || N < 1 || pos0 < 0) return TUCKER_ATTN_INVALID_ARG;
-  if ((Kcache_out == nullptr) != (Vcache_out == nullptr)) return TUCKER_ATTN_INVALID_ARG;
   const tucker_attn_config& f = c->cfg;
+  if (f.shared_kv ? Vcache_out != nullptr : (Kcache_out == nullptr) != (Vcache_out == nullptr))
+    return TUCKER_ATTN_INVALID_ARG;
   if (Kcache_out && (Lmax < 1 || (long)pos0 + N > Lmax)) return TUCKER_ATTN_INVALID_ARG;
   if (f.use_rope && (long)pos0 + N > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
   if ((long)B * pad64(N) > (1l << 30) / 64 || B > 65535) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
@@ -290,7 +294,7 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
 
   GemmArgs g;
   std::memset(&g, 0, sizeof(g));
-  g.A = ws.Wcat; g.lda = c->dp; g.M = c->R2 + 2 * c->D;
+  g.A = ws.Wcat; g.lda = c->dp; g.M = c->R2 + (f.shared_kv ? 1 : 2) * c->D; g.shared_kv = f.shared_kv;
   g.Bsrc = X; g.ldb = f.d_model; g.K = f.d_model;
   g.Bsz = B; g.N = N; g.Npad = Npad; g.src_padded = 0;
   g.epi = 0;
@@ -333,10 +337,10 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
 int tucker_attn_decode(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x, void* y, void* Kcache,
                        void* Vcache, int32_t Lmax, const int32_t* kv_len, int32_t B, void* workspace,
                        size_t workspace_bytes, void* hip_stream) {
-  if (!c || !weights_ok(w) || !x || !y || !Kcache || !Vcache || !kv_len || !workspace)
-    return TUCKER_ATTN_INVALID_ARG;
+  if (!c || !weights_ok(c, w) || !x || !y || !Kcache || !kv_len || !workspace) return TUCKER_ATTN_INVALID_ARG;
   if (B < 1 || B > 32 || Lmax < 1) return TUCKER_ATTN_INVALID_ARG;
   const tucker_attn_config& f = c->cfg;
+  if (f.shared_kv ? Vcache != nullptr : Vcache == nullptr) return TUCKER_ATTN_INVALID_ARG;
   for (int b = 0; b < B; ++b) {
     if (kv_len[b] < 1 || kv_len[b] > Lmax) return TUCKER_ATTN_INVALID_ARG;
     if (f.use_rope && kv_len[b] > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
@@ -359,7 +363,7 @@ int tucker_attn_decode(tucker_attn_ctx* c, const tucker_attn_weights* w, const v
 
   GemmArgs g;
   std::memset(&g, 0, sizeof(g));
-  g.A = ws.Wcat; g.lda = c->dp; g.M = c->R2 + 2 * c->D;
+  g.A = ws.Wcat; g.lda = c->dp; g.M = c->R2 + (f.shared_kv ? 1 : 2) * c->D; g.shared_kv = f.shared_kv;
   g.Bsrc = x; g.ldb = f.d_model; g.K = f.d_model;
   g.Bsz = B; g.N = 1; g.Npad = 1; g.src_padded = 0;
   g.epi = 0;
@@ -376,7 +380,7 @@ int tucker_attn_decode(tucker_attn_ctx* c, const tucker_attn_weights* w, const v
   d.Qlat = ws.Qlat; d.Gt = ws.Gt; d.Qh = ws.Qh; d.Kcache = Kcache; d.Vcache = Vcache;
   d.part_m = ws.pm; d.part_l = ws.pl; d.part_o = ws.po; d.O = ws.O; d.rope = c->rope; d.rope_ld = f.max_positions;
   d.Bsz = B; d.nH = f.n_heads; d.HB = pad32(f.n_heads) / 32; d.R2 = c->R2; d.r3 = f.r3; d.rt3 = f.rt3;
-  d.D = c->D; d.Lmax = Lmax; d.nsplit = decode_nsplit(B);
+  d.D = c->D; d.Lmax = Lmax; d.nsplit = decode_nsplit(B); d.shared_kv = f.shared_kv;
   for (int b = 0; b < B; ++b) d.kv_len[b] = kv_len[b];
   if (launch_decode_qhat(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
   rec.after("decode_query");

@@ -140,18 +140,68 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeArgs p) {
     for (int i = 0; i < PT; ++i) {
       const long n = (long)tile * BC + srow[i];
       const uint32_t ko = (live && scol[i] < p.r3) ? (uint32_t)((n * p.r3 + scol[i]) * (long)sizeof(T)) : 0x80000000u;
-      const uint32_t vo = (live && scol[i] < p.rt3) ? (uint32_t)((n * p.rt3 + scol[i]) * (long)sizeof(T)) : 0x80000000u;
+      const uint32_t vo = (live && !p.shared_kv && scol[i] < p.rt3) ? (uint32_t)((n * p.rt3 + scol[i]) * (long)sizeof(T)) : 0x80000000u;
       r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, ko, 0, 0);
       r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, vo, 0, 0);
     }
+  };
+  // Shared key-value latent: the cache row is the value as it stands and becomes the key once
+  // rotated to its position.  The rotation entries of the tile that is staged next are fetched
+  // one product phase ahead; a chunk of CE channels needs CE/4 table entries.
+  constexpr int QPC = CE / 4;                                     // table entries per 16-byte chunk
+  const bool rotate_on_load = p.shared_kv && p.rope != nullptr;
+  f32x4 rot[PT][QPC];
+  auto rot_load = [&](int tile) {
+    if (!rotate_on_load) return;
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int n = max(min(tile * BC + srow[i], Lb - 1), 0);     // rows past the end are zeros: any entry serves
+      const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope) + (long)(scol[i] / 4) * p.rope_ld + n;
+#pragma unroll
+      for (int q = 0; q < QPC; ++q) rot[i][q] = tab[(long)q * p.rope_ld];
+    }
+  };
+  auto rotated = [&](const u32x4& raw, const f32x4 (&cs)[QPC]) -> u32x4 {
+    float x[CE];
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        x[2 * j] = __uint_as_float(raw[j] << 16);
+        x[2 * j + 1] = __uint_as_float(raw[j] & 0xffff0000u);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) x[j] = __uint_as_float(raw[j]);
+    }
+#pragma unroll
+    for (int q = 0; q < QPC; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; e += 2) {
+        const float x0 = x[4 * q + e], x1 = x[4 * q + e + 1];
+        x[4 * q + e] = x0 * cs[q][e] - x1 * cs[q][e + 1];
+        x[4 * q + e + 1] = x0 * cs[q][e + 1] + x1 * cs[q][e];
+      }
+    u32x4 out;
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        f32x2 two = {x[2 * j], x[2 * j + 1]};
+        out[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) out[j] = __float_as_uint(x[j]);
+    }
+    return out;
   };
   auto s_store = [&](const Set& r, int stage) {
     T* ks = smem + (long)stage * L::kStageElems;
     T* vs = ks + L::kTileElems;
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
-      *reinterpret_cast<u32x4*>(ks + srow[i] * L::kRowElems + scol[i]) = r.k[i];
-      *reinterpret_cast<u32x4*>(vs + srow[i] * L::kRowElems + scol[i]) = r.v[i];
+      const u32x4 kv = rotate_on_load ? rotated(r.k[i], rot[i]) : r.k[i];
+      *reinterpret_cast<u32x4*>(ks + srow[i] * L::kRowElems + scol[i]) = kv;
+      *reinterpret_cast<u32x4*>(vs + srow[i] * L::kRowElems + scol[i]) = p.shared_kv ? r.k[i] : r.v[i];
     }
   };
 
@@ -237,22 +287,25 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeArgs p) {
   // would keep all workgroups on the same memory channels.  Each workgroup therefore starts at
   // its own tile of its slice and wraps around (the online softmax does not care about order).
   const int cnt = max(t_last - t_first, 0);
-  const int rot = cnt > 0 ? (int)((split * 5u + b * 3u) % (unsigned)cnt) : 0;
+  const int first = cnt > 0 ? (int)((split * 5u + b * 3u) % (unsigned)cnt) : 0;
   auto tile_at = [&](int j) {                                     // j-th tile in this workgroup's order
-    int r = j + rot;
+    int r = j + first;
     if (r >= cnt) r -= cnt;
     return j < cnt ? t_first + r : t_last;                        // past the end: a dead tile
   };
   g_load(ra, tile_at(0));
   g_load(rb, tile_at(1));
+  rot_load(tile_at(0));
   s_store(ra, 0);
   g_load(ra, tile_at(2));
   __syncthreads();
   for (int j = 0; j < cnt; j += 2) {
+    rot_load(tile_at(j + 1));
     compute(tile_at(j), 0);
     s_store(rb, 1);
     g_load(rb, tile_at(j + 3));
     __syncthreads();
+    rot_load(tile_at(j + 2));
     if (j + 1 < cnt) compute(tile_at(j + 1), 1);
     s_store(ra, 0);
     g_load(ra, tile_at(j + 4));

@@ -94,6 +94,29 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, in
       store_frag<T>(dst, to_frag<T>(acc));
     } else if (m0 < g.R2 + g.D) {                               // ---- K, rotated
       const int c0 = m0 - g.R2;
+      if (g.shared_kv) {
+        // shared key-value latent: the unrotated block is the value block and the cache row
+        if (g.Vt != nullptr) {
+          T* base = static_cast<T*>(g.Vt) + (long)b * g.D * g.Npad + (n & ~31) + acc_pos(n & 31);
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) store1(base + (long)(c0 + 8 * q + 4 * h + e) * g.Npad, acc[4 * q + e]);
+        }
+        if (g.Kcache != nullptr && valid) {
+          T* row = static_cast<T*>(g.Kcache) + ((long)b * g.Lmax + pos) * g.r3;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            int c = c0 + 8 * q + 4 * h;
+            if (c + 3 < g.r3 && (g.r3 % 4) == 0)
+              store4(row + c, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+            else
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (c + e < g.r3) store1(row + c + e, acc[4 * q + e]);
+          }
+        }
+      }
       if (g.rope != nullptr) {
         // (cos, sin) of two adjacent pairs per load, all four loads issued before the first use;
         // rows of padding tokens hold zeros, so any table row serves them
@@ -114,7 +137,7 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, in
         T* dst = static_cast<T*>(g.Kr) + (long)tp * g.D + c0 + 16 * h;
         store_frag<T>(dst, to_frag<T>(acc));
       }
-      if (g.Kcache != nullptr && valid) {
+      if (g.Kcache != nullptr && valid && !g.shared_kv) {
         T* row = static_cast<T*>(g.Kcache) + ((long)b * g.Lmax + pos) * g.r3;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -355,7 +378,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
     for (int j = 0; j < NB; ++j) {
       int m0 = m_tile + (wm * MB + i) * 32;
       int tp = t_tile + (wn * NB + j) * 32 + lr;
-      const int Mp = (g.epi == 0) ? g.R2 + 2 * g.D : pad32(g.M);
+      const int Mp = (g.epi == 0) ? g.R2 + (g.shared_kv ? 1 : 2) * g.D : pad32(g.M);
       if (m0 >= Mp) continue;
       if (g.ksplit > 1) {
         if (tp < TP) {
@@ -375,7 +398,7 @@ template <typename T>
 __global__ __launch_bounds__(64) void splitk_reduce_kernel(GemmArgs g) {
   const int lane = threadIdx.x, h = lane / 32, lr = lane % 32;
   const int TP = g.Bsz * g.Npad;
-  const int Mp = (g.epi == 0) ? g.R2 + 2 * g.D : pad32(g.M);
+  const int Mp = (g.epi == 0) ? g.R2 + (g.shared_kv ? 1 : 2) * g.D : pad32(g.M);
   const int m0 = blockIdx.x * 32, tp = blockIdx.y * 32 + lr;
   f32x16 acc;
 #pragma unroll
@@ -416,7 +439,7 @@ static hipError_t launch_one(const GemmArgs& a, int m_rows, hipStream_t s) {
 }
 
 hipError_t launch_gemm(int dtype, const GemmArgs& a, int tile_n, hipStream_t s) {
-  const int m_rows = (a.epi == 0) ? a.R2 + 2 * a.D : a.M;
+  const int m_rows = (a.epi == 0) ? a.R2 + (a.shared_kv ? 1 : 2) * a.D : a.M;
   if (dtype == 0) {
     if (tile_n >= 128) return launch_one<float, 128, 128, 2, 2>(a, m_rows, s);
     if (tile_n >= 64) return launch_one<float, 128, 64, 2, 2>(a, m_rows, s);

@@ -57,6 +57,7 @@ struct GemmArgs {
   const float4* rope;
   int rope_ld;
   int pos0;
+  int shared_kv;                // 1: no V rows in A; the K block also yields Vt, and the cache row, UNROTATED
   int decode;                   // 1: one token per sequence, position/cache row from kv_pos[b]
   int kv_pos[32];
   // Z / Y
@@ -95,6 +96,7 @@ struct DecodeArgs {
   const float4* rope; // [D/4][rope_ld] as in GemmArgs, or null
   int rope_ld;
   int Bsz, nH, HB, R2, r3, rt3, D, Lmax, nsplit;
+  int shared_kv;       // 1: Kcache holds the unrotated latent, which is also the value; Vcache is null
   int kv_len[32];
 };
 

@@ -38,8 +38,9 @@ class Layer:
         self.ctx = ta.tucker_attn_create(
             d_model=w.d_model, n_heads=w.n_heads, d_head=w.d_head, r1=w.r1, r2=w.r2, r3=w.r3,
             rt1=rt1, rt2=rt2, rt3=rt3, causal=w.causal, rope_base=w.rope_base, dtype=w.dtype,
-            max_positions=max_positions)
-        self.weights = {k: to_device(inp[k], w.dtype) for k in W_KEYS}
+            max_positions=max_positions, shared_kv=w.shared_kv)
+        # with a shared key-value projection the library never reads the value basis: it gets none
+        self.weights = {k: to_device(inp[k], w.dtype) for k in W_KEYS if not (w.shared_kv and k == "Ut3")}
         self._ws = None
 
     def close(self):
@@ -66,7 +67,7 @@ class Layer:
         ta.tucker_attn_forward(self.ctx, self.weights, X, Y, pos0, Kc, Vc, ws)
         return Y
 
-    def decode(self, x: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, kv_len, y=None) -> torch.Tensor:
+    def decode(self, x: torch.Tensor, Kc: torch.Tensor, Vc: Optional[torch.Tensor], kv_len, y=None) -> torch.Tensor:
         if y is None:
             y = torch.empty_like(x)
         ws = self.workspace(ta.tucker_attn_decode_workspace_bytes(self.ctx, x.shape[0]))

@@ -55,6 +55,7 @@ class Workload:
     rt2: int = 0
     rt3: int = 0
     pos0: int = 0
+    shared_kv: bool = False     # shared key-value down-projection: value basis = key basis, one cache
 
     def ranks_post(self):
         return (self.rt1 or self.r1, self.rt2 or self.r2, self.rt3 or self.r3)
@@ -81,6 +82,13 @@ WORKLOADS: Dict[str, Workload] = {
     "decode_32k": Workload("decode_32k", B=16, N=1, d_model=4096, n_heads=32, d_head=128,
                            r1=8, r2=128, r3=128, dtype="bf16", causal=True, rope_base=1e4,
                            seed=4, recipe="orthonormal", mode="decode", kv_len=32768),
+    # shared key-value down-projection (Section "KV Caching"): configs 4 and 5 with one latent
+    "llama7b_n4096_shared_kv": Workload("llama7b_n4096_shared_kv", B=2, N=4096, d_model=4096, n_heads=32,
+                                        d_head=128, r1=8, r2=128, r3=128, dtype="bf16", causal=True,
+                                        rope_base=1e4, seed=7, recipe="orthonormal", shared_kv=True),
+    "decode_32k_shared_kv": Workload("decode_32k_shared_kv", B=16, N=1, d_model=4096, n_heads=32, d_head=128,
+                                     r1=8, r2=128, r3=128, dtype="bf16", causal=True, rope_base=1e4,
+                                     seed=8, recipe="orthonormal", mode="decode", kv_len=32768, shared_kv=True),
     # the paper's own rank shapes (tables of Section "Experiments"): unequal query and key ranks on
     # the GPT-2 layer, and its LLaMA3-1B layer with r1 = nH and RoPE base 5e5
     "gpt2_r8_128_64": Workload("gpt2_r8_128_64", B=8, N=1024, d_model=768, n_heads=12, d_head=64,
@@ -143,7 +151,8 @@ def make_inputs(w: Workload) -> Dict[str, np.ndarray]:
     Keys: X [B,N,d]; C [r1,r2,r3]; U1 [nH,r1]; U2 [d,r2]; U3 [d,r3];
           Ct [rt1,rt2,rt3]; Ut1 [nH,rt1]; Ut2 [d,rt2]; Ut3 [d,rt3].
     Decode workloads add: Kcache, Vcache [B,kv_len,r3/rt3] (row kv_len-1 zero, to be
-    written by the decode step itself) and kv_len [B] int32; X is then [B,1,d].
+    written by the decode step itself) and kv_len [B] int32; X is then [B,1,d].  With
+    shared_kv, Ut3 is a copy of U3 and the decode cache is the single Lcache [B,kv_len,r3].
     """
     rng = np.random.default_rng(w.seed)
     d, nH = w.d_model, w.n_heads
@@ -180,6 +189,12 @@ def make_inputs(w: Workload) -> Dict[str, np.ndarray]:
     else:
         raise ValueError(w.recipe)
 
+    if w.shared_kv:
+        # the value basis is the key basis (it is still drawn, so that the stream of random numbers
+        # of a workload does not depend on this switch)
+        if rt3 != r3:
+            raise ValueError("shared key-value projection needs rt3 == r3")
+        Ut3 = U3.copy()
     out = dict(X=x, C=C, U1=U1, U2=U2, U3=U3, Ct=Ct, Ut1=Ut1, Ut2=Ut2, Ut3=Ut3)
 
     if w.mode == "decode":
@@ -195,8 +210,11 @@ def make_inputs(w: Workload) -> Dict[str, np.ndarray]:
             vc[b] = rng.standard_normal((L, rt3), dtype=np.float32)
         kc[:, L - 1, :] = 0.0
         vc[:, L - 1, :] = 0.0
-        out["Kcache"] = kc
-        out["Vcache"] = vc
+        if w.shared_kv:
+            out["Lcache"] = kc                  # one cache: the unrotated latent rows
+        else:
+            out["Kcache"] = kc
+            out["Vcache"] = vc
         out["kv_len"] = np.full((w.B,), L, dtype=np.int32)
 
     for k, v in out.items():

@@ -144,6 +144,105 @@ def test_config5_decode_scaled_and_full_size():
     check_decode(base, inp, "decode full")
 
 
+# ---- shared key-value down-projection (one latent serves as K and V; one unrotated cache) --------
+
+def run_decode_shared(w, inp):
+    with Layer(w, inp, max_positions=int(max(inp["kv_len"])) + 1) as layer:
+        x = to_device(inp["X"][:, 0], w.dtype)
+        Lc = to_device(inp["Lcache"], w.dtype)
+        y = layer.decode(x, Lc, None, inp["kv_len"])
+        torch.cuda.synchronize()
+        return to_host(y), to_host(Lc)
+
+
+def check_decode_shared(w, inp, what):
+    y, Lc = run_decode_shared(w, inp)
+    y_ref, L_ref = orc.decode_step_shared_kv(inp["X"][:, 0], inp["Lcache"], inp["kv_len"], wl.weights_of(inp),
+                                             w.d_head, w.rope_base)
+    check(y, y_ref, w.dtype, what)
+    for b in range(w.B):
+        L = int(inp["kv_len"][b])
+        check(Lc[b, L - 1], L_ref[b, L - 1], w.dtype, what + " new latent row")
+        assert np.array_equal(Lc[b, : L - 1], inp["Lcache"][b, : L - 1])      # old rows untouched
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rope", [1e4, None])
+def test_shared_kv_prefill_and_its_cache(dtype, rope):
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=150, dtype=dtype, rope_base=rope, seed=21, shared_kv=True, pos0=3)
+    inp = wl.make_inputs(w)
+    with Layer(w, inp, max_positions=w.pos0 + w.N + 8) as layer:
+        X = to_device(inp["X"], w.dtype)
+        Lc = torch.zeros((w.B, 200, w.r3), dtype=X.dtype, device="cuda")
+        Y = layer.forward(X, pos0=w.pos0, Kc=Lc, Vc=None)
+        torch.cuda.synchronize()
+        check(to_host(Y), oracle_forward(w, inp), dtype, "shared-KV prefill")
+        lat = inp["X"].astype(np.float64) @ inp["U3"].astype(np.float64)     # unrotated latent rows
+        got = to_host(Lc)
+        check(got[:, w.pos0:w.pos0 + w.N], lat, dtype, "shared-KV cache rows")
+        assert not got[:, : w.pos0].any() and not got[:, w.pos0 + w.N:].any()
+
+
+def test_shared_kv_llama_shape_scaled_full_and_full_size_sampled():
+    base = wl.WORKLOADS["llama7b_n4096_shared_kv"]
+    w = wl.scaled(base, B=1, N=320)
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), w.dtype, "shared-KV llama B=1 N=320")
+    inp = wl.make_inputs(base)
+    y = run_forward(base, inp)
+    rows = [0, 1, 64, 2047, 2048, 4094, 4095]
+    ref = oracle_forward(base, inp, rows=rows, batches=[1])
+    check(y[[1]][:, rows], ref, base.dtype, "shared-KV llama full")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rope", [1e4, None])
+def test_shared_kv_decode_ragged(dtype, rope):
+    base = wl.scaled(wl.WORKLOADS["decode_32k_shared_kv"], d_model=256, n_heads=8, d_head=32, r1=4, r2=64, r3=48,
+                     B=3, kv_len=333, dtype=dtype, rope_base=rope, seed=22)
+    inp = wl.make_inputs(base)
+    inp["kv_len"] = np.array([333, 1, 130], dtype=np.int32)
+    check_decode_shared(base, inp, "shared-KV decode ragged")
+
+
+def test_shared_kv_decode_full_size():
+    base = wl.WORKLOADS["decode_32k_shared_kv"]
+    inp = wl.make_inputs(base)
+    check_decode_shared(base, inp, "shared-KV decode full")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_shared_kv_decode_continues_a_prefill(dtype):
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=97, dtype=dtype, seed=23, shared_kv=True)
+    inp = wl.make_inputs(w)
+    full = oracle_forward(w, inp)                                              # causal: row N-1 = the decoded token
+    with Layer(w, inp, max_positions=w.N + 1) as layer:
+        X = to_device(inp["X"], w.dtype)
+        Lc = torch.zeros((w.B, 128, w.r3), dtype=X.dtype, device="cuda")
+        Xp = X[:, : w.N - 1].contiguous()
+        layer.forward(Xp, pos0=0, Kc=Lc, Vc=None)
+        y = layer.decode(X[:, w.N - 1].contiguous(), Lc, None, [w.N] * w.B)
+        torch.cuda.synchronize()
+        check(to_host(y), full[:, w.N - 1], dtype, "shared-KV decode after prefill")
+
+
+def test_shared_kv_argument_errors():
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], N=32, shared_kv=True)
+    inp = wl.make_inputs(w)
+    with Layer(w, inp) as layer:
+        X = to_device(inp["X"], w.dtype)
+        Y = torch.empty_like(X)
+        Kc = torch.zeros((w.B, 64, w.r3), dtype=X.dtype, device="cuda")
+        ws = layer.workspace(ta.tucker_attn_workspace_bytes(layer.ctx, w.B, w.N))
+        # a value cache has no meaning here
+        assert ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, 0, Kc, Kc, ws, check=False) == -1
+        x = X[:, 0].contiguous()
+        wsd = layer.workspace(ta.tucker_attn_decode_workspace_bytes(layer.ctx, w.B))
+        assert ta.tucker_attn_decode(layer.ctx, layer.weights, x, torch.empty_like(x), Kc, Kc, [5], wsd, check=False) == -1
+    with pytest.raises(ta.TuckerAttnError):                                     # value rank must equal key rank
+        ta.tucker_attn_create(d_model=64, n_heads=2, d_head=32, r1=2, r2=32, r3=32, rt3=16, shared_kv=True)
+
+
 # ---- edge cases ----------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 129])

@@ -293,6 +293,38 @@ def test_decode_equals_last_row_of_causal_prefill(rope):
         close(Vn[b, : lens[b]], V[b, : lens[b]])
 
 
+@pytest.mark.parametrize("rope", [None, 25.0])
+def test_shared_kv_decode_equals_last_row_of_prefill_with_one_basis(rope):
+    # Sharing U3 between the two Tucker factorizations (value basis := key basis) is the shared
+    # key-value down-projection; the one-cache decode must reproduce the last row of the ordinary
+    # prefill evaluated with Ut3 = U3, and its cache must be the UNROTATED latent X U3.
+    rng = RNG(62)
+    d, nH, N, Lmax = 8, 3, 7, 9
+    w = rand_weights(rng, d, nH, (2, 3, 4))
+    w["Ut3"] = w["U3"].copy()
+    X = rng.standard_normal((2, N, d))
+    full = orc.per_head_forward(X, w, 4, True, rope_base=rope)
+    Lat = X @ w["U3"]
+    Lc = np.zeros((2, Lmax, 4))
+    lens = np.array([N, N - 3])
+    for b in range(2):
+        Lc[b, : lens[b] - 1] = Lat[b, : lens[b] - 1]
+    xs = np.stack([X[b, lens[b] - 1] for b in range(2)])
+    w_no_value_basis = {k: v for k, v in w.items()}
+    w_no_value_basis["Ut3"] = np.full_like(w["U3"], np.nan)          # must not be read
+    y, Ln = orc.decode_step_shared_kv(xs, Lc, lens, w_no_value_basis, 4, rope_base=rope)
+    for b in range(2):
+        close(y[b], full[b, lens[b] - 1], 1e-10)
+        close(Ln[b, : lens[b]], Lat[b, : lens[b]])
+    # and it agrees with the two-cache decode fed the rotated and the plain copy of the same latent
+    K, V = orc.latent_kv(X, w, rope)
+    Kc, Vc = np.zeros((2, Lmax, 4)), np.zeros((2, Lmax, 4))
+    for b in range(2):
+        Kc[b, : lens[b] - 1], Vc[b, : lens[b] - 1] = K[b, : lens[b] - 1], V[b, : lens[b] - 1]
+    y2, _, _ = orc.decode_step(xs, Kc, Vc, lens, w, 4, rope_base=rope)
+    close(y, y2, 1e-10)
+
+
 # --- robustness of the softmax ---------------------------------------------------------------------
 
 def test_sharp_and_shifted_scores_stay_finite_and_exact():
