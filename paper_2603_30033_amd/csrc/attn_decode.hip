@@ -71,7 +71,8 @@ template <typename T, int D, int BC> struct DecLds {
 __device__ __forceinline__ float lds_elem(const float* p) { return *p; }
 __device__ __forceinline__ bf16 lds_elem(const bf16* p) { return *p; }
 
-template <typename T, int D, int BC, int HB>
+// SH: shared key-value latent (one unrotated cache; keys rotated as a tile is staged)
+template <typename T, int D, int BC, int HB, bool SH>
 __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeArgs p) {
   constexpr int CB = D / 32, NB = BC / 32;
   constexpr int CE = 16 / sizeof(T);
@@ -140,28 +141,35 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeArgs p) {
     for (int i = 0; i < PT; ++i) {
       const long n = (long)tile * BC + srow[i];
       const uint32_t ko = (live && scol[i] < p.r3) ? (uint32_t)((n * p.r3 + scol[i]) * (long)sizeof(T)) : 0x80000000u;
-      const uint32_t vo = (live && !p.shared_kv && scol[i] < p.rt3) ? (uint32_t)((n * p.rt3 + scol[i]) * (long)sizeof(T)) : 0x80000000u;
+      const uint32_t vo = (live && !SH && scol[i] < p.rt3) ? (uint32_t)((n * p.rt3 + scol[i]) * (long)sizeof(T)) : 0x80000000u;
       r.k[i] = __builtin_amdgcn_raw_buffer_load_b128(krs, ko, 0, 0);
       r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, vo, 0, 0);
     }
   };
   // Shared key-value latent: the cache row is the value as it stands and becomes the key once
-  // rotated to its position.  The rotation entries of the tile that is staged next are fetched
-  // one product phase ahead; a chunk of CE channels needs CE/4 table entries.
+  // rotated to its position n = tile*BC + row.  The rotation by n is the rotation by tile*BC
+  // followed by the rotation by row: the second is the same for every tile and is fetched once per
+  // thread (its chunks sit at fixed rows and channels of a tile), the first is one table entry per
+  // channel quad per tile.  Both come from the context's table.
   constexpr int QPC = CE / 4;                                     // table entries per 16-byte chunk
-  const bool rotate_on_load = p.shared_kv && p.rope != nullptr;
-  f32x4 rot[PT][QPC];
-  auto rot_load = [&](int tile) {
-    if (!rotate_on_load) return;
+  const bool rotate_on_load = SH && p.rope != nullptr;
+  f32x4 rot_row[PT][QPC], rot_tile[QPC];
+  if (rotate_on_load) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
-      const int n = max(min(tile * BC + srow[i], Lb - 1), 0);     // rows past the end are zeros: any entry serves
-      const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope) + (long)(scol[i] / 4) * p.rope_ld + n;
+      const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope) + (long)(scol[i] / 4) * p.rope_ld + min(srow[i], p.rope_ld - 1);
 #pragma unroll
-      for (int q = 0; q < QPC; ++q) rot[i][q] = tab[(long)q * p.rope_ld];
+      for (int q = 0; q < QPC; ++q) rot_row[i][q] = tab[(long)q * p.rope_ld];
     }
+  }
+  auto rot_load = [&](int tile) {                                 // every chunk of a thread has the same channels
+    if (!rotate_on_load) return;
+    const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope) + (long)(scol[0] / 4) * p.rope_ld +
+                       min((long)tile * BC, (long)p.rope_ld - 1); // a dead tile holds zeros: any entry serves
+#pragma unroll
+    for (int q = 0; q < QPC; ++q) rot_tile[q] = tab[(long)q * p.rope_ld];
   };
-  auto rotated = [&](const u32x4& raw, const f32x4 (&cs)[QPC]) -> u32x4 {
+  auto rotated = [&](const u32x4& raw, const f32x4 (&row)[QPC]) -> u32x4 {
     float x[CE];
     if constexpr (sizeof(T) == 2) {
 #pragma unroll
@@ -177,9 +185,11 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeArgs p) {
     for (int q = 0; q < QPC; ++q)
 #pragma unroll
       for (int e = 0; e < 4; e += 2) {
+        const float ca = row[q][e], sa = row[q][e + 1], cb = rot_tile[q][e], sb = rot_tile[q][e + 1];
+        const float c = ca * cb - sa * sb, sn = sa * cb + ca * sb;   // angle addition
         const float x0 = x[4 * q + e], x1 = x[4 * q + e + 1];
-        x[4 * q + e] = x0 * cs[q][e] - x1 * cs[q][e + 1];
-        x[4 * q + e + 1] = x0 * cs[q][e + 1] + x1 * cs[q][e];
+        x[4 * q + e] = x0 * c - x1 * sn;
+        x[4 * q + e + 1] = x0 * sn + x1 * c;
       }
     u32x4 out;
     if constexpr (sizeof(T) == 2) {
@@ -199,9 +209,9 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeArgs p) {
     T* vs = ks + L::kTileElems;
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
-      const u32x4 kv = rotate_on_load ? rotated(r.k[i], rot[i]) : r.k[i];
+      const u32x4 kv = rotate_on_load ? rotated(r.k[i], rot_row[i]) : r.k[i];
       *reinterpret_cast<u32x4*>(ks + srow[i] * L::kRowElems + scol[i]) = kv;
-      *reinterpret_cast<u32x4*>(vs + srow[i] * L::kRowElems + scol[i]) = p.shared_kv ? r.k[i] : r.v[i];
+      *reinterpret_cast<u32x4*>(vs + srow[i] * L::kRowElems + scol[i]) = SH ? r.k[i] : r.v[i];
     }
   };
 
@@ -398,10 +408,10 @@ hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, hipStream_t s) {
   return hipErrorInvalidValue;
 }
 
-template <typename T, int D, int BC, int HB>
-static hipError_t attn_one(const DecodeArgs& a, hipStream_t s) {
+template <typename T, int D, int BC, int HB, bool SH>
+static hipError_t attn_one_sh(const DecodeArgs& a, hipStream_t s) {
   size_t smem = DecLds<T, D, BC>::kBytes;
-  auto kern = decode_attn_kernel<T, D, BC, HB>;
+  auto kern = decode_attn_kernel<T, D, BC, HB, SH>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -411,6 +421,10 @@ static hipError_t attn_one(const DecodeArgs& a, hipStream_t s) {
   }
   hipLaunchKernelGGL(kern, dim3(a.nsplit, a.Bsz), dim3(256), smem, s, a);
   return hipGetLastError();
+}
+template <typename T, int D, int BC, int HB>
+static hipError_t attn_one(const DecodeArgs& a, hipStream_t s) {
+  return a.shared_kv ? attn_one_sh<T, D, BC, HB, true>(a, s) : attn_one_sh<T, D, BC, HB, false>(a, s);
 }
 template <typename T, int BC>
 static hipError_t attn_dispatch(const DecodeArgs& a, hipStream_t s) {
