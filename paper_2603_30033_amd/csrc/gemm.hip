@@ -404,14 +404,24 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(GemmArgs g) {
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   if (tp < TP) {
-    for (int z = 0; z < g.ksplit; ++z) {
-      const float* src = g.part + ((long)z * TP + tp) * Mp + m0 + 4 * h;
+    // four splits at a time: their 16 loads are issued before the first add, and the sums are still
+    // formed in split order
+    for (int z0 = 0; z0 < g.ksplit; z0 += 4) {
+      f32x4 v[4][4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        f32x4 v = *reinterpret_cast<const f32x4*>(src + 8 * q);
+      for (int u = 0; u < 4; ++u) {
+        const int z = min(z0 + u, g.ksplit - 1);
+        const float* src = g.part + ((long)z * TP + tp) * Mp + m0 + 4 * h;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) acc[4 * q + r] += v[r];
+        for (int q = 0; q < 4; ++q) v[u][q] = *reinterpret_cast<const f32x4*>(src + 8 * q);
       }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (z0 + u < g.ksplit)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[4 * q + r] += v[u][q][r];
     }
   }
   epilogue_block<T>(g, acc, m0, tp);
@@ -446,7 +456,8 @@ hipError_t launch_gemm(int dtype, const GemmArgs& a, int tile_n, hipStream_t s) 
     return launch_one<float, 128, 32, 4, 1>(a, m_rows, s);
   }
   // 129..192 weight rows (three 64-wide factor blocks): one 192-row tile instead of one full and one
-  // half-empty 128-row tile, and the token rows are read once (only when the token tiles alone give every compute unit two workgroups)
+  // half-empty 128-row tile, and the token rows are read once (only when the token tiles alone give
+  // every compute unit two workgroups)
   if (tile_n == 64 && m_rows > 128 && m_rows <= 192 && ((long)a.Bsz * a.Npad + 63) / 64 >= 512)
     return launch_one<bf16, 192, 64, 2, 2>(a, m_rows, s);
   if (tile_n >= 128) return launch_one<bf16, 128, 128, 2, 2>(a, m_rows, s);
