@@ -184,7 +184,8 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
   // Online softmax with a lazily updated reference exponent: probabilities are formed as
   // exp2(s - m_ref) where m_ref is the row maximum seen when it was last refreshed; it is
   // refreshed (and O, l rescaled) only when a tile's maximum exceeds it by more than kLazy, so
-  // the common tile does no rescaling.  Values stay below 2^kLazy; the final O / l is exact.
+  // the common tile does no rescaling.  The subtraction costs nothing: a score block is accumulated
+  // on top of -m_ref.  Values stay below 2^kLazy; the final O / l is exact.
   constexpr float kLazy = 8.f;
   f32x16 oacc[QB][CB];
   float m_ref[QB], l_run[QB];
@@ -210,6 +211,11 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
   // pair of interval t+1 is staged meanwhile; one barrier per interval, n_tiles+1 intervals.
   f32x16 s[QB][NB];
   Frag<T> pf[QB][NB];
+  f32x16 negm[QB];                                              // -reference in all 16 registers: start of a score block
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) negm[qb][e] = 0.f;
   // MFMA phase: O += V(tile-1) P(tile-1) (if PV) and then S = K(tile) Qhat (if SS), as ONE stream
   // of operand fragments read from LDS through a ring of kRing registers sets: the read of
   // fragment i+kRing-1 is issued before the product with fragment i, so a product never waits
@@ -226,14 +232,6 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
       const int j = i - NPV;
       return load_frag<T>(kbase + (j / CB) * 32 * L::kKRowElems + (j % CB) * 32);
     };
-    if (SS) {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) s[qb][nb][e] = 0.f;
-    }
     Frag<T> ring[kRing];
 #pragma unroll
     for (int i = 0; i < kRing - 1 && i < TOT; ++i) ring[i] = fetch(i);
@@ -248,7 +246,11 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
       } else {
         const int j = i - NPV;
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) mma32(s[qb][j / CB], f, qf[qb][j % CB]);
+        for (int qb = 0; qb < QB; ++qb) {
+          // a score block starts from -reference, so the products form S - reference directly
+          if (j % CB == 0) mma32_from(s[qb][j / CB], negm[qb], f, qf[qb][0]);
+          else mma32(s[qb][j / CB], f, qf[qb][j % CB]);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -281,23 +283,28 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[qb][nb][e]);
-      mx = halves_max(mx);
-      const bool upd = (tile == 0 || mx - m_ref[qb] > kLazy) && mx != -INFINITY;
+      mx = halves_max(mx);                                      // relative to the reference in force
+      const bool upd = (tile == 0 || mx > kLazy) && mx != -INFINITY;
       if (__builtin_amdgcn_ballot_w64(upd) != 0ull) {
-        const float m_new = upd ? mx : m_ref[qb];
-        const float alpha = fast_exp2(m_ref[qb] - m_new);       // tile 0: O and l are still zero
-        m_ref[qb] = m_new;
+        const float delta = upd ? mx : 0.f;                     // new reference = old + delta
+        const float alpha = tile == 0 ? 1.f : fast_exp2(-delta); // tile 0: O and l are still zero
+        m_ref[qb] += delta;
         l_run[qb] *= alpha;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
           for (int e = 0; e < 16; ++e) oacc[qb][cb][e] *= alpha;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) s[qb][nb][e] -= delta;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) negm[qb][e] = -m_ref[qb];
       }
-      const float mr = m_ref[qb];
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) s[qb][nb][e] = fast_exp2(s[qb][nb][e] - mr);
+        for (int e = 0; e < 16; ++e) s[qb][nb][e] = fast_exp2(s[qb][nb][e]);
         pf[qb][nb] = to_frag<T>(s[qb][nb]);
         l_run[qb] = frag_sum(pf[qb][nb], l_run[qb]);
       }

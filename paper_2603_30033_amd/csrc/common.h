@@ -53,6 +53,21 @@ __device__ __forceinline__ void mma32(f32x16& acc, const Frag<float>& a, const F
       acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][j], b.v[i][j], acc, 0, 0, 0);
 }
 
+// out = c + A_frag * B_frag over one 32-slice (c is read, not overwritten: a block that starts
+// from a constant need not be copied first)
+__device__ __forceinline__ void mma32_from(f32x16& out, const f32x16& c, const Frag<bf16>& a, const Frag<bf16>& b) {
+  out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v[0], b.v[0], c, 0, 0, 0);
+  out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v[1], b.v[1], out, 0, 0, 0);
+}
+__device__ __forceinline__ void mma32_from(f32x16& out, const f32x16& c, const Frag<float>& a, const Frag<float>& b) {
+  out = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[0][0], b.v[0][0], c, 0, 0, 0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (i + j > 0) out = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[i][j], b.v[i][j], out, 0, 0, 0);
+}
+
 // accumulator block -> operand fragment (acc order), with rounding to T
 __device__ __forceinline__ Frag<float> to_frag_f32(const f32x16& a) {
   Frag<float> f;
