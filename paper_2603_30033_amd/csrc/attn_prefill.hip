@@ -14,6 +14,7 @@
 // cross-lane movement (see the fragment model in common.h).
 //
 // Workgroup = QW x HW waves = HW heads x (32*QB*QW) queries; K/V tile = BC keys, double buffered.
+// Built as 8 waves: 4 heads x 2 query blocks of 32; waves w and w+4 share a SIMD.
 #include <type_traits>
 
 #include "common.h"

@@ -4,14 +4,19 @@
 //                (Definition "Latent RoPE": the key rotation is computed once for all heads)
 //   latent merge Z(tok) = sum_i G~_i O_i(tok)                          (head merge through the
 //                post-softmax core, from the contraction of H1 and H2 over heads)
-//   output       Y(tok) = U~2 Z(tok)                                   (output-mode basis)
+//   output       Y(tok) = U~2 Z(tok)                                   (output-mode basis; prefill-sized
+//                calls with a short contraction use the dedicated kernel of out_proj.hip)
+// With a shared key-value latent the projection has no V rows: the K block's accumulators are
+// stored unrotated as V (and as the cache row) before they are rotated.
 // All three compute acc[m][tok] = sum_k A[m][k] B[tok][k] with the weight side as MFMA rows
 // and tokens as MFMA columns, so that an accumulator lane owns one token and four
 // consecutive output channels per register quad.
 //
 // Tiling: workgroup = 4 waves, tile TM x TN (weights x tokens), contraction staged through
-// LDS in slices of 64 elements, double buffered; LDS rows are padded by 16 bytes so that
-// the 16-byte fragment reads of 8 consecutive rows fall into distinct bank groups.
+// LDS in slices of 64 elements, double buffered, fed from a ring of register slots that keeps
+// three slices in flight; LDS rows are padded by 16 bytes so that the 16-byte fragment reads of
+// 8 consecutive rows fall into distinct bank groups.  Token counts of a decode step run the same
+// kernel with the contraction split over workgroups and a second kernel that sums the parts.
 #include <type_traits>
 
 #include "common.h"

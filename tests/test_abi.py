@@ -79,3 +79,18 @@ def test_workspace_sizes_and_host_side_argument_checks():
         assert lib.tucker_attn_decode(ctx, C.byref(w), 256, 256, 256, 256, 8, lens, 2, 256, 16, None) == -3
     finally:
         ta.tucker_attn_destroy(ctx)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one-GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_shared_kv_config_is_validated_on_the_host():
+    with pytest.raises(ta.TuckerAttnError) as e:                  # value rank must equal the key rank
+        ta.tucker_attn_create(**_cfg(rt3=16, shared_kv=True))
+    assert "status -1 " in str(e.value)
+    ctx = ta.tucker_attn_create(**_cfg(shared_kv=True))
+    ta.tucker_attn_destroy(ctx)
