@@ -89,7 +89,7 @@ def cpu_baseline(w):
         f = flops(ws)["total"]
         sample = f"decode step of {ws.B} of the {w.B} sequences at kv_len={w.kv_len} (cache given, as for the GPU)"
     else:
-        n = min(w.N, 2048)
+        n = min(w.N, 4096)
         b = 1 if w.N >= 1024 else min(w.B, 16)
         ws = wl.scaled(w, B=b, N=n)
         inp = wl.make_inputs(ws)
