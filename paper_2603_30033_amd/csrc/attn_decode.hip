@@ -412,13 +412,8 @@ template <typename T, int D, int BC, int HB, bool SH>
 static hipError_t attn_one_sh(const DecodeArgs& a, hipStream_t s) {
   size_t smem = DecLds<T, D, BC>::kBytes;
   auto kern = decode_attn_kernel<T, D, BC, HB, SH>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsOnce lds_once;                                       // one per kernel instantiation
+  if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
   hipLaunchKernelGGL(kern, dim3(a.nsplit, a.Bsz), dim3(256), smem, s, a);
   return hipGetLastError();
 }

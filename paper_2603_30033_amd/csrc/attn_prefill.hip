@@ -372,13 +372,8 @@ static hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
   dim3 grid(((a.nH + HW - 1) / HW) * a.Bsz, (a.N + TQ - 1) / TQ);
   size_t smem = AttnLds<T, D, BC>::kBytes;
   auto kern = attn_prefill_kernel<T, D, QB, BC, QW, HW>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsOnce lds_once;                                       // one per kernel instantiation
+  if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
   hipLaunchKernelGGL(kern, grid, dim3(64 * QW * HW), smem, s, a);
   return hipGetLastError();
 }

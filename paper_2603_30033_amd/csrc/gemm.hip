@@ -438,13 +438,8 @@ static hipError_t launch_one(const GemmArgs& a, int m_rows, hipStream_t s) {
   dim3 grid((m_rows + TM - 1) / TM, (TP + TN - 1) / TN, a.ksplit > 1 ? a.ksplit : 1);
   size_t smem = 2ul * (TM + TN) * Lds<T>::kRowBytes;
   auto kern = gemm_kernel<T, TM, TN, WGM, WGN>;
-  static bool attr_done = false;   // raise the dynamic LDS limit once per instantiation
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsOnce lds_once;                                       // one per kernel instantiation
+  if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.ksplit <= 1) return e;

@@ -136,13 +136,8 @@ static hipError_t out_one(const GemmArgs& a, hipStream_t s) {
   dim3 grid((m_tiles + per - 1) / per, t_tiles);
   size_t smem = OutLds<T, KB, TM>::kBytes;
   auto kern = out_proj_kernel<T, KB, TM>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsOnce lds_once;                                       // one per kernel instantiation
+  if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
   hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, a, per);
   return hipGetLastError();
 }

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace ta {
 
 // ---- weight preparation (head-mixed cores, transposed factor matrices) ------------------
@@ -99,6 +101,25 @@ struct DecodeArgs {
   int shared_kv;       // 1: Kcache holds the unrotated latent, which is also the value; Vcache is null
   int kv_len[32];
 };
+
+// Raise a kernel's dynamic-LDS limit to `bytes`, once per kernel and device (the attribute belongs
+// to the device's copy of the code object).  `once` is a static of the launcher of that one
+// kernel instantiation.  Safe to call from several host threads.
+struct LdsOnce {
+  static constexpr int kMaxDevices = 64;
+  std::atomic<unsigned char> done[kMaxDevices];
+};
+template <typename K>
+inline hipError_t allow_dynamic_lds(LdsOnce& once, K kernel, size_t bytes) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < LdsOnce::kMaxDevices;
+  if (tracked && once.done[dev].load(std::memory_order_acquire)) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess && tracked) once.done[dev].store(1, std::memory_order_release);
+  return e;
+}
 
 hipError_t launch_prep(int dtype, const PrepArgs& a, hipStream_t s);
 bool out_proj_supported(int dtype, const GemmArgs& a);
