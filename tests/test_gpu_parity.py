@@ -390,6 +390,49 @@ def test_decode_edge_lengths_and_many_heads(dtype):
     check_decode(base, inp, "decode 40 heads")
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_small_configurations(seed):
+    """Random shapes inside the library's limits: ranks that are not multiples of the tile sizes, head
+    counts that do not fill a head group, lengths around tile edges, every mode switch."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = ["f32", "bf16"][seed % 2]
+    shared = bool(rng.integers(0, 2))
+    r3 = int(rng.choice([8, 16, 24, 40, 48, 64, 72, 96, 128]))
+    rt3 = r3 if shared else int(rng.choice([8, 16, 32, 56, 64, 104, 128]))
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=int(rng.integers(1, 4)), N=int(rng.integers(1, 260)),
+                  d_model=int(rng.choice([64, 96, 128, 200, 256])), n_heads=int(rng.integers(1, 11)),
+                  d_head=int(rng.choice([16, 32, 64])), r1=int(rng.integers(1, 5)), r2=int(rng.choice([8, 20, 32, 48, 80])),
+                  r3=r3, rt1=int(rng.integers(1, 5)), rt2=int(rng.choice([8, 24, 32, 64, 100])), rt3=rt3,
+                  dtype=dtype, causal=bool(rng.integers(0, 2)), rope_base=[None, 1e4, 5e5][int(rng.integers(0, 3))],
+                  seed=2000 + seed, shared_kv=shared, pos0=int(rng.integers(0, 50)))
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), dtype, repr(w))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_small_decode_configurations(seed):
+    rng = np.random.default_rng(3000 + seed)
+    dtype = ["f32", "bf16"][seed % 2]
+    shared = bool(seed % 4 >= 2)
+    es = 4 if dtype == "f32" else 2
+    ranks = [r for r in (8, 16, 24, 40, 48, 64, 96, 128) if (r * es) % 16 == 0]
+    r3 = int(rng.choice(ranks))
+    rt3 = r3 if shared else int(rng.choice(ranks))
+    B = int(rng.integers(1, 6))
+    kv = int(rng.integers(1, 600))
+    w = wl.scaled(wl.WORKLOADS["decode_32k_shared_kv" if shared else "decode_32k"], B=B, kv_len=kv,
+                  d_model=int(rng.choice([64, 128, 200])), n_heads=int(rng.integers(1, 41)), d_head=32,
+                  r1=int(rng.integers(1, 5)), r2=int(rng.choice([8, 32, 48])), r3=r3, rt1=int(rng.integers(1, 5)),
+                  rt2=int(rng.choice([8, 32, 64])), rt3=rt3, dtype=dtype, rope_base=[None, 1e4][int(rng.integers(0, 2))],
+                  seed=4000 + seed, recipe="fan_in")
+    inp = wl.make_inputs(w)
+    inp["kv_len"] = rng.integers(1, kv + 1, size=B).astype(np.int32)
+    if shared:
+        check_decode_shared(w, inp, repr(w))
+    else:
+        check_decode(w, inp, repr(w))
+
+
 def test_gpu_side_argument_errors():
     w = wl.scaled(wl.WORKLOADS["tiny_f32"], N=32)
     inp = wl.make_inputs(w)
