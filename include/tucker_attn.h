@@ -142,15 +142,49 @@ int tucker_attn_decode(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
                        const int32_t *kv_len, int32_t B,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Device pointers that receive the weight gradients, fp32 whatever the storage type (they are
+ * sums over all tokens); caller-owned, overwritten (not accumulated into). */
+typedef struct {
+  float *dC;    /* [r1, r2, r3]    */
+  float *dU1;   /* [nH, r1]        */
+  float *dU2;   /* [d,  r2]        */
+  float *dU3;   /* [d,  r3]        with shared_kv: key path plus value path */
+  float *dCt;   /* [rt1, rt2, rt3] */
+  float *dUt1;  /* [nH, rt1]       */
+  float *dUt2;  /* [d,  rt2]       */
+  float *dUt3;  /* [d,  rt3]       must be NULL with shared_kv (no such weight) */
+} tucker_attn_grads;
+
+/* Bytes of device workspace tucker_attn_backward needs; 0 if an argument is invalid. */
+size_t tucker_attn_backward_workspace_bytes(const tucker_attn_ctx *ctx, int32_t B, int32_t N);
+
 /*
- * Optional per-kernel timing for benchmarks.  While enabled, forward/decode bracket every
+ * Gradients of the prefill forward (the paper trains the layer -- Section "Experiments" -- and
+ * times a backward pass; the gradient is the derivative of the forward of Definition "Tucker
+ * Attention" with latent RoPE, evaluated flash-style: attention probabilities are recomputed
+ * from a saved log-sum-exp, never stored).  For loss = sum(dY * Y):
+ *   X    device [B, N, d]   in: the forward input
+ *   dY   device [B, N, d]   in: upstream gradient, storage type
+ *   dX   device [B, N, d]   out: gradient of X, storage type
+ *   grads                   out: gradients of the eight weight arrays (seven with shared_kv), fp32
+ * The call is self-contained: it re-runs the forward up to the head merge inside its own
+ * workspace (no state of an earlier tucker_attn_forward call is used), then the backward kernels.
+ * Same shape limits as forward, and B * roundup(N, 64) <= 2^21 tokens.
+ */
+int tucker_attn_backward(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
+                         const void *X, const void *dY, void *dX, const tucker_attn_grads *grads,
+                         int32_t B, int32_t N, int32_t pos0,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Optional per-kernel timing for benchmarks.  While enabled, forward/backward/decode bracket every
  * kernel they launch with HIP events recorded on the caller's stream; tucker_attn_profile_read
  * synchronises those events and returns, for the LAST call, the kernel count and for each
  * kernel its name and duration.  Event recording perturbs end-to-end time slightly, so
  * throughput is measured with profiling disabled.
  *   names   host array of n_max pointers, receives static strings (nullable)
  *   ms      host array of n_max floats (nullable)
- * Returns the number of kernels of the last call (<= 16) or a negative status.
+ * Returns the number of kernels of the last call (<= 40) or a negative status.
  */
 int tucker_attn_profile_enable(tucker_attn_ctx *ctx, int32_t on);
 int tucker_attn_profile_read(tucker_attn_ctx *ctx, const char **names, float *ms, int32_t n_max);

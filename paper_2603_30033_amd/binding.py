@@ -1,7 +1,7 @@
 """Thin ctypes binding of libtucker_attn.so: argument marshalling only.
 
 Same names as the C ABI (include/tucker_attn.h).  PyTorch supplies device memory and the
-HIP stream; every step of the forward pass runs in the library's kernels.  There is no
+HIP stream; every step of the forward and backward passes runs in the library's kernels.  There is no
 fallback: if the shared library is missing or a call fails, an exception is raised.
 """
 from __future__ import annotations
@@ -19,6 +19,7 @@ TUCKER_ATTN_BF16 = 1
 EXPORTED = [
     "tucker_attn_create", "tucker_attn_destroy", "tucker_attn_workspace_bytes",
     "tucker_attn_decode_workspace_bytes", "tucker_attn_forward", "tucker_attn_decode",
+    "tucker_attn_backward_workspace_bytes", "tucker_attn_backward",
     "tucker_attn_profile_enable", "tucker_attn_profile_read", "tucker_attn_status_string",
 ]
 
@@ -37,6 +38,13 @@ class tucker_attn_config(C.Structure):
 
 class tucker_attn_weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("C", "U1", "U2", "U3", "Ct", "Ut1", "Ut2", "Ut3")]
+
+
+GRAD_KEYS = ("dC", "dU1", "dU2", "dU3", "dCt", "dUt1", "dUt2", "dUt3")
+
+
+class tucker_attn_grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in GRAD_KEYS]
 
 
 _lib = None
@@ -69,6 +77,12 @@ def load_library() -> C.CDLL:
                                        C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32,
                                        C.c_void_p, C.c_size_t, C.c_void_p]
     lib.tucker_attn_decode.restype = C.c_int
+    lib.tucker_attn_backward_workspace_bytes.argtypes = [ctx_p, C.c_int32, C.c_int32]
+    lib.tucker_attn_backward_workspace_bytes.restype = C.c_size_t
+    lib.tucker_attn_backward.argtypes = [ctx_p, C.POINTER(tucker_attn_weights), C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.POINTER(tucker_attn_grads), C.c_int32, C.c_int32, C.c_int32,
+                                         C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.tucker_attn_backward.restype = C.c_int
     lib.tucker_attn_profile_enable.argtypes = [ctx_p, C.c_int32]
     lib.tucker_attn_profile_enable.restype = C.c_int
     lib.tucker_attn_profile_read.argtypes = [ctx_p, C.POINTER(C.c_char_p), C.POINTER(C.c_float), C.c_int32]
@@ -160,14 +174,35 @@ def tucker_attn_decode(ctx: int, weights: Dict, x, y, Kcache, Vcache, kv_len: Li
     return st
 
 
+def tucker_attn_backward_workspace_bytes(ctx: int, B: int, N: int) -> int:
+    return int(load_library().tucker_attn_backward_workspace_bytes(ctx, B, N))
+
+
+def tucker_attn_backward(ctx: int, weights: Dict, X, dY, dX, grads: Dict, pos0: int = 0, workspace=None,
+                         stream=None, check: bool = True) -> int:
+    """X, dY, dX: contiguous device tensors [B, N, d] of the storage type; grads: dict of contiguous fp32
+    device tensors keyed dC, dU1, dU2, dU3, dCt, dUt1, dUt2 and (unless the latent is shared) dUt3,
+    shaped like the weights; all are overwritten."""
+    B, N = int(X.shape[0]), int(X.shape[1])
+    ws = _weights_struct(weights)
+    gs = tucker_attn_grads(*[_ptr(grads.get(k)) for k in GRAD_KEYS])
+    st = load_library().tucker_attn_backward(ctx, C.byref(ws), X.data_ptr(), dY.data_ptr(), dX.data_ptr(),
+                                             C.byref(gs), B, N, int(pos0),
+                                             _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                             _stream_ptr(stream))
+    if check:
+        _check(st, "tucker_attn_backward")
+    return st
+
+
 def tucker_attn_profile_enable(ctx: int, on: bool) -> None:
     _check(load_library().tucker_attn_profile_enable(ctx, int(bool(on))), "tucker_attn_profile_enable")
 
 
 def tucker_attn_profile_read(ctx: int) -> List[Tuple[str, float]]:
-    names = (C.c_char_p * 16)()
-    ms = (C.c_float * 16)()
-    n = load_library().tucker_attn_profile_read(ctx, names, ms, 16)
+    names = (C.c_char_p * 40)()
+    ms = (C.c_float * 40)()
+    n = load_library().tucker_attn_profile_read(ctx, names, ms, 40)
     if n < 0:
         _check(n, "tucker_attn_profile_read")
     return [(names[i].decode(), float(ms[i])) for i in range(n)]

@@ -15,7 +15,7 @@
 using namespace ta;
 
 namespace {
-constexpr int kMaxKernels = 16;
+constexpr int kMaxKernels = 40;
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 }  // namespace
@@ -74,6 +74,81 @@ PrefillWs carve_prefill(const tucker_attn_ctx* c, void* ws, int B, int N) {
   w.Vt = cv.take<char>((size_t)B * c->D * Npad * c->es);
   w.O = cv.take<char>(TP * f.n_heads * c->D * c->es);
   w.Z = cv.take<char>(TP * c->RT2 * c->es);
+  w.bytes = cv.off;
+  return w;
+}
+
+struct BackwardWs {
+  PrefillWs f;
+  float *lse, *delta, *dKp, *dVp, *dG, *dGt, *part;
+  void *Vr, *Krt, *Ut2T, *Gtil_t, *G2, *Wb, *dZ, *Qr, *dO, *dQ, *Qt, *dOt, *dQt, *dLat;
+  void *Xt, *dYt, *dLat_t, *Zt, *Qlat_t, *dZt, *Ot;
+  int LW;            // width of the latent-gradient rows: R2 + D (shared latent) or R2 + 2 D
+  int hpg, n_hg;     // heads per group / number of groups of the key-value gradient kernel
+  int ks_w, ks_u, ks_g;   // contraction splits of the weight-gradient products
+  size_t bytes;
+};
+
+// contraction split of a token-contracted product with `tiles` output tiles and K tokens
+int grad_ksplit(long tiles, long K) {
+  long want = (512 + tiles - 1) / tiles;
+  const long nk = (K + 63) / 64;
+  if (want > 16) want = 16;
+  if (want > nk) want = nk;
+  return want < 1 ? 1 : (int)want;
+}
+
+BackwardWs carve_backward(const tucker_attn_ctx* c, void* ws, int B, int N) {
+  const tucker_attn_config& f = c->cfg;
+  const size_t Npad = pad64(N), TP = (size_t)B * Npad, es = c->es;
+  const size_t nHD = (size_t)f.n_heads * c->D;
+  BackwardWs w;
+  w.f = carve_prefill(c, ws, B, N);
+  Carver cv{static_cast<char*>(ws), w.f.bytes};
+  w.LW = c->R2 + (f.shared_kv ? 1 : 2) * c->D;
+  const long ktiles = (long)((Npad + 127) / 128) * B;
+  int n_hg = (int)((1024 + ktiles - 1) / ktiles);
+  if (n_hg > f.n_heads) n_hg = f.n_heads;
+  if (n_hg < 1) n_hg = 1;
+  w.hpg = (f.n_heads + n_hg - 1) / n_hg;
+  w.n_hg = (f.n_heads + w.hpg - 1) / w.hpg;
+  w.lse = cv.take<float>((size_t)B * f.n_heads * Npad * 4);
+  w.delta = cv.take<float>((size_t)B * f.n_heads * Npad * 4);
+  w.Vr = cv.take<char>(TP * c->D * es);
+  w.Krt = cv.take<char>(TP * c->D * es);
+  w.Ut2T = cv.take<char>((size_t)c->RT2 * c->dp * es);
+  w.Gtil_t = cv.take<char>(nHD * c->RT2 * es);
+  w.G2 = cv.take<char>((size_t)c->R2 * nHD * es);
+  w.Wb = cv.take<char>((size_t)c->dp * w.LW * es);
+  w.dZ = cv.take<char>(TP * c->RT2 * es);
+  w.Qr = cv.take<char>(TP * nHD * es);
+  w.dO = cv.take<char>(TP * nHD * es);
+  w.dQ = cv.take<char>(TP * nHD * es);
+  w.Qt = cv.take<char>(TP * nHD * es);
+  w.dOt = cv.take<char>(TP * nHD * es);
+  w.dQt = cv.take<char>(TP * nHD * es);
+  w.dKp = cv.take<float>((size_t)w.n_hg * TP * c->D * 4);
+  w.dVp = cv.take<float>((size_t)w.n_hg * TP * c->D * 4);
+  w.dLat = cv.take<char>(TP * w.LW * es);
+  w.Xt = cv.take<char>((size_t)c->dp * TP * es);
+  w.dYt = cv.take<char>((size_t)c->dp * TP * es);
+  w.dLat_t = cv.take<char>((size_t)w.LW * TP * es);
+  w.Zt = cv.take<char>((size_t)c->RT2 * TP * es);
+  w.Qlat_t = cv.take<char>((size_t)c->R2 * TP * es);
+  w.dZt = cv.take<char>((size_t)c->RT2 * TP * es);
+  w.Ot = cv.take<char>(nHD * TP * es);
+  w.dG = cv.take<float>((size_t)c->R2 * nHD * 4);
+  w.dGt = cv.take<float>((size_t)c->RT2 * nHD * 4);
+  const long mt = (f.d_model + 127) / 128;
+  w.ks_w = grad_ksplit(mt * ((w.LW + 63) / 64), (long)TP);
+  w.ks_u = grad_ksplit(mt * ((c->RT2 + 63) / 64), (long)TP);
+  const int rmax = c->R2 > c->RT2 ? c->R2 : c->RT2;
+  w.ks_g = grad_ksplit(((rmax + 127) / 128) * (long)((nHD + 63) / 64), (long)TP);
+  size_t part = (size_t)w.ks_w * w.LW * pad32(f.d_model);
+  const size_t p2 = (size_t)w.ks_u * c->RT2 * pad32(f.d_model), p3 = (size_t)w.ks_g * nHD * rmax;
+  if (p2 > part) part = p2;
+  if (p3 > part) part = p3;
+  w.part = cv.take<float>(part * 4);
   w.bytes = cv.off;
   return w;
 }
@@ -182,6 +257,55 @@ bool weights_ok(const tucker_attn_ctx* c, const tucker_attn_weights* w) {
   return c && w && w->C && w->U1 && w->U2 && w->U3 && w->Ct && w->Ut1 && w->Ut2 && (w->Ut3 || c->cfg.shared_kv);
 }
 
+// prep, factor projection, attention and head merge of a prefill call: everything up to Z.  The
+// backward pass calls it with buffers for the extra outputs it needs (value rows, transposed keys,
+// log-sum-exp); the forward passes null for those.
+int forward_core(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* X, int B, int N, int pos0,
+                 void* Kcache_out, void* Vcache_out, int Lmax, const PrefillWs& ws, void* Vr, void* Krt, float* lse,
+                 hipStream_t s, Recorder& rec, const void** ut2_out, long* ut2_ld_out) {
+  const tucker_attn_config& f = c->cfg;
+  const int Npad = pad64(N);
+  const long TP = (long)B * Npad;
+  const void* ut2;
+  long ut2_ld;
+  PrepArgs pa = make_prep(c, w, ws.Gt, ws.Gtil2, ws.Wcat, ws.Ut2p, &ut2, &ut2_ld);
+  if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("prep_weights");
+
+  GemmArgs g;
+  std::memset(&g, 0, sizeof(g));
+  g.A = ws.Wcat; g.lda = c->dp; g.M = c->R2 + (f.shared_kv ? 1 : 2) * c->D; g.shared_kv = f.shared_kv;
+  g.Bsrc = X; g.ldb = f.d_model; g.K = f.d_model;
+  g.Bsz = B; g.N = N; g.Npad = Npad; g.src_padded = 0;
+  g.epi = 0;
+  g.Qlat = ws.Qlat; g.R2 = c->R2; g.Kr = ws.Kr; g.D = c->D; g.Vt = ws.Vt; g.Vr = Vr; g.Krt = Krt;
+  g.Kcache = Kcache_out; g.Vcache = Vcache_out; g.Lmax = Lmax; g.r3 = f.r3; g.rt3 = f.rt3;
+  g.rope = c->rope; g.rope_ld = f.max_positions; g.pos0 = pos0; g.decode = 0; g.ksplit = 1;
+  if (launch_gemm(f.dtype, g, pick_tile_n((g.M + 127) / 128, TP, g.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("factor_projection");
+
+  AttnArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.Qlat = ws.Qlat; a.Gt = ws.Gt; a.Kr = ws.Kr; a.Vt = ws.Vt; a.O = ws.O; a.lse = lse;
+  a.rope = c->rope; a.rope_ld = f.max_positions;
+  a.Bsz = B; a.N = N; a.Npad = Npad; a.nH = f.n_heads; a.R2 = c->R2; a.r3 = f.r3; a.D = c->D;
+  a.causal = f.causal; a.pos0 = pos0;
+  if (launch_attn_prefill(f.dtype, a, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("attention");
+
+  GemmArgs z;
+  std::memset(&z, 0, sizeof(z));
+  z.A = ws.Gtil2; z.lda = (long)f.n_heads * c->D; z.M = c->RT2;
+  z.Bsrc = ws.O; z.ldb = (long)f.n_heads * c->D; z.K = f.n_heads * c->D;
+  z.Bsz = B; z.N = N; z.Npad = Npad; z.src_padded = 1;
+  z.epi = 1; z.Out = ws.Z; z.ldo = c->RT2; z.ksplit = 1; z.R2 = 0; z.D = 0;
+  if (launch_gemm(f.dtype, z, pick_tile_n((z.M + 127) / 128, TP, z.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("latent_merge");
+  *ut2_out = ut2;
+  *ut2_ld_out = ut2_ld;
+  return TUCKER_ATTN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -285,41 +409,12 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
   const long TP = (long)B * Npad;
   Recorder rec{c, s, c->profile != 0};
   if (rec.begin() != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-
   const void* ut2;
   long ut2_ld;
-  PrepArgs pa = make_prep(c, w, ws.Gt, ws.Gtil2, ws.Wcat, ws.Ut2p, &ut2, &ut2_ld);
-  if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("prep_weights");
-
-  GemmArgs g;
-  std::memset(&g, 0, sizeof(g));
-  g.A = ws.Wcat; g.lda = c->dp; g.M = c->R2 + (f.shared_kv ? 1 : 2) * c->D; g.shared_kv = f.shared_kv;
-  g.Bsrc = X; g.ldb = f.d_model; g.K = f.d_model;
-  g.Bsz = B; g.N = N; g.Npad = Npad; g.src_padded = 0;
-  g.epi = 0;
-  g.Qlat = ws.Qlat; g.R2 = c->R2; g.Kr = ws.Kr; g.D = c->D; g.Vt = ws.Vt;
-  g.Kcache = Kcache_out; g.Vcache = Vcache_out; g.Lmax = Lmax; g.r3 = f.r3; g.rt3 = f.rt3;
-  g.rope = c->rope; g.rope_ld = f.max_positions; g.pos0 = pos0; g.decode = 0; g.ksplit = 1;
-  if (launch_gemm(f.dtype, g, pick_tile_n((g.M + 127) / 128, TP, g.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("factor_projection");
-
-  AttnArgs a;
-  std::memset(&a, 0, sizeof(a));
-  a.Qlat = ws.Qlat; a.Gt = ws.Gt; a.Kr = ws.Kr; a.Vt = ws.Vt; a.O = ws.O; a.rope = c->rope; a.rope_ld = f.max_positions;
-  a.Bsz = B; a.N = N; a.Npad = Npad; a.nH = f.n_heads; a.R2 = c->R2; a.r3 = f.r3; a.D = c->D;
-  a.causal = f.causal; a.pos0 = pos0;
-  if (launch_attn_prefill(f.dtype, a, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("attention");
-
-  GemmArgs z;
-  std::memset(&z, 0, sizeof(z));
-  z.A = ws.Gtil2; z.lda = (long)f.n_heads * c->D; z.M = c->RT2;
-  z.Bsrc = ws.O; z.ldb = (long)f.n_heads * c->D; z.K = f.n_heads * c->D;
-  z.Bsz = B; z.N = N; z.Npad = Npad; z.src_padded = 1;
-  z.epi = 1; z.Out = ws.Z; z.ldo = c->RT2; z.ksplit = 1; z.R2 = 0; z.D = 0;
-  if (launch_gemm(f.dtype, z, pick_tile_n((z.M + 127) / 128, TP, z.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("latent_merge");
+  if (int st = forward_core(c, w, X, B, N, pos0, Kcache_out, Vcache_out, Lmax, ws, nullptr, nullptr, nullptr, s, rec,
+                            &ut2, &ut2_ld);
+      st != TUCKER_ATTN_OK)
+    return st;
 
   GemmArgs y;
   std::memset(&y, 0, sizeof(y));
@@ -331,6 +426,186 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
                                                        : launch_gemm(f.dtype, y, pick_tile_n((y.M + 127) / 128, TP, y.K), s);
   if (ye != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
   rec.after("output_projection");
+  return TUCKER_ATTN_OK;
+}
+
+size_t tucker_attn_backward_workspace_bytes(const tucker_attn_ctx* c, int32_t B, int32_t N) {
+  if (!c || B < 1 || N < 1) return 0;
+  return carve_backward(c, nullptr, B, N).bytes;
+}
+
+int tucker_attn_backward(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* X, const void* dY, void* dX,
+                         const tucker_attn_grads* gr, int32_t B, int32_t N, int32_t pos0, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  if (!c || !weights_ok(c, w) || !X || !dY || !dX || !gr || !workspace) return TUCKER_ATTN_INVALID_ARG;
+  const tucker_attn_config& f = c->cfg;
+  if (!gr->dC || !gr->dU1 || !gr->dU2 || !gr->dU3 || !gr->dCt || !gr->dUt1 || !gr->dUt2) return TUCKER_ATTN_INVALID_ARG;
+  if (f.shared_kv ? gr->dUt3 != nullptr : gr->dUt3 == nullptr) return TUCKER_ATTN_INVALID_ARG;
+  if (B < 1 || N < 1 || pos0 < 0) return TUCKER_ATTN_INVALID_ARG;
+  if (f.use_rope && (long)pos0 + N > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
+  if ((long)B * pad64(N) > (1l << 21) || B > 65535) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
+  BackwardWs ws = carve_backward(c, workspace, B, N);
+  if (workspace_bytes < ws.bytes) return TUCKER_ATTN_WORKSPACE_TOO_SMALL;
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int Npad = pad64(N);
+  const long TP = (long)B * Npad;
+  const int nHD = f.n_heads * c->D, LW = ws.LW, es = c->es;
+  Recorder rec{c, s, c->profile != 0};
+  if (rec.begin() != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+
+  // ---- forward intermediates: Qlat, K, V (three layouts), O, log-sum-exp, Z ----------------------------
+  const void* ut2;
+  long ut2_ld;
+  if (int st = forward_core(c, w, X, B, N, pos0, nullptr, nullptr, 0, ws.f, ws.Vr, ws.Krt, ws.lse, s, rec, &ut2, &ut2_ld);
+      st != TUCKER_ATTN_OK)
+    return st;
+
+  // ---- weights in the layouts of the backward products ------------------------------------------------------
+  {
+    PrepArgs pa;
+    std::memset(&pa, 0, sizeof(pa));
+    // U~2^T [RT2][dp]
+    add_job(pa, w->Ut2, nullptr, ws.Ut2T, 1, f.d_model, f.rt2, 1, c->dp, c->RT2, 0, c->dp, 1, 0, 1.f);
+    // G~t[i][c][b] = G~_i[b][c], fragment-major blocks of (c, b), b in natural order
+    add_job(pa, w->Ct, w->Ut1, ws.Gtil_t, f.rt1, f.rt2, f.rt3, f.n_heads, c->RT2, c->D, (long)c->D * c->RT2, c->RT2, 1, 0,
+            1.f, 1);
+    // G2[b][i*D + c] = G_i[b][c] / sqrt(d_head), c in acc order like the stored query gradient
+    add_job(pa, w->C, w->U1, ws.G2, f.r1, f.r2, f.r3, f.n_heads, c->R2, c->D, c->D, nHD, 0, 1,
+            (float)(1.0 / std::sqrt((double)f.d_head)));
+    // Wb[j][.] = [U2 | U3 | U~3] rows, zero padded to the latent-gradient row layout
+    char* wb = static_cast<char*>(ws.Wb);
+    add_job(pa, w->U2, nullptr, wb, 1, f.d_model, f.r2, 1, c->dp, c->R2, 0, LW, 0, 0, 1.f);
+    add_job(pa, w->U3, nullptr, wb + (size_t)c->R2 * es, 1, f.d_model, f.r3, 1, c->dp, c->D, 0, LW, 0, 0, 1.f);
+    if (!f.shared_kv)
+      add_job(pa, w->Ut3, nullptr, wb + (size_t)(c->R2 + c->D) * es, 1, f.d_model, f.rt3, 1, c->dp, c->D, 0, LW, 0, 0, 1.f);
+    if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("prep_weights_bwd");
+  }
+
+  // ---- dZ = dY U~2 -----------------------------------------------------------------------------------------------
+  {
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A = ws.Ut2T; g.lda = c->dp; g.M = c->RT2;
+    g.Bsrc = dY; g.ldb = f.d_model; g.K = f.d_model;
+    g.Bsz = B; g.N = N; g.Npad = Npad; g.src_padded = 0;
+    g.epi = 1; g.Out = ws.dZ; g.ldo = c->RT2; g.ksplit = 1;
+    if (launch_gemm(f.dtype, g, pick_tile_n((g.M + 127) / 128, TP, g.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("grad_z");
+  }
+
+  // ---- attention backward -------------------------------------------------------------------------------------
+  BwdArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.Qlat = ws.f.Qlat; a.Gt = ws.f.Gt; a.dZ = ws.dZ; a.Gtil_t = ws.Gtil_t; a.Kr = ws.f.Kr; a.Vr = ws.Vr; a.Krt = ws.Krt;
+  a.O = ws.f.O; a.lse = ws.lse; a.delta = ws.delta; a.Qr = ws.Qr; a.dO = ws.dO; a.Qt = ws.Qt; a.dOt = ws.dOt;
+  a.dQ = ws.dQ; a.dQt = ws.dQt; a.dKp = ws.dKp; a.dVp = ws.dVp; a.rope = c->rope; a.rope_ld = f.max_positions;
+  a.Bsz = B; a.N = N; a.Npad = Npad; a.nH = f.n_heads; a.R2 = c->R2; a.RT2 = c->RT2; a.D = c->D;
+  a.causal = f.causal; a.pos0 = pos0; a.hpg = ws.hpg; a.n_hg = ws.n_hg;
+  if (launch_bwd_dq(f.dtype, a, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("attention_bwd_dq");
+  if (launch_bwd_dkv(f.dtype, a, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("attention_bwd_dkv");
+  {
+    KvReduceArgs k;
+    std::memset(&k, 0, sizeof(k));
+    k.dKp = ws.dKp; k.dVp = ws.dVp; k.dLat = ws.dLat; k.ld = LW; k.colK = c->R2; k.colV = c->R2 + c->D;
+    k.rope = c->rope; k.rope_ld = f.max_positions;
+    k.Bsz = B; k.N = N; k.Npad = Npad; k.D = c->D; k.n_hg = ws.n_hg; k.pos0 = pos0; k.shared_kv = f.shared_kv;
+    if (launch_kv_reduce(f.dtype, k, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("grad_kv_latent");
+  }
+
+  // ---- dQlat = sum_i dQ_i G_i^T / sqrt(d_head), into the first R2 columns of the latent-gradient rows ---------
+  {
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A = ws.G2; g.lda = nHD; g.M = c->R2;
+    g.Bsrc = ws.dQ; g.ldb = nHD; g.K = nHD;
+    g.Bsz = B; g.N = N; g.Npad = Npad; g.src_padded = 1;
+    g.epi = 1; g.Out = ws.dLat; g.ldo = LW; g.ksplit = 1;
+    if (launch_gemm(f.dtype, g, pick_tile_n((g.M + 127) / 128, TP, g.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("grad_q_latent");
+  }
+
+  // ---- dX = [dQlat | dKlat | dVlat] [U2 | U3 | U~3]^T ----------------------------------------------------------
+  {
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A = ws.Wb; g.lda = LW; g.M = f.d_model;
+    g.Bsrc = ws.dLat; g.ldb = LW; g.K = LW;
+    g.Bsz = B; g.N = N; g.Npad = Npad; g.src_padded = 1;
+    g.epi = 2; g.Out = dX; g.ldo = f.d_model; g.ksplit = 1;
+    if (launch_gemm(f.dtype, g, pick_tile_n((g.M + 127) / 128, TP, g.K), s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("grad_x");
+  }
+
+  // ---- token-minor copies for the products that contract over tokens ------------------------------------------
+  auto transpose = [&](const void* src, long ld, int cols, int cols_pad, int src_padded, int unperm, void* dst) {
+    TransposeArgs t;
+    std::memset(&t, 0, sizeof(t));
+    t.src = src; t.ld = ld; t.cols = cols; t.cols_pad = cols_pad;
+    t.Bsz = B; t.N = N; t.Npad = Npad; t.src_padded = src_padded; t.unperm = unperm; t.dst = dst;
+    return launch_transpose(f.dtype, t, s);
+  };
+  if (transpose(X, f.d_model, f.d_model, c->dp, 0, 0, ws.Xt) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  if (transpose(dY, f.d_model, f.d_model, c->dp, 0, 0, ws.dYt) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  if (transpose(ws.dLat, LW, LW, LW, 1, 0, ws.dLat_t) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  if (transpose(ws.f.Z, c->RT2, c->RT2, c->RT2, 1, 0, ws.Zt) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  if (transpose(ws.f.Qlat, c->R2, c->R2, c->R2, 1, 1, ws.Qlat_t) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  if (transpose(ws.dZ, c->RT2, c->RT2, c->RT2, 1, 0, ws.dZt) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  if (transpose(ws.f.O, nHD, nHD, nHD, 1, 1, ws.Ot) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  rec.after("token_minor_copies");
+
+  // ---- products over tokens: out[m][n] = sum_t At[m][t] Bt[n][t] -----------------------------------------------
+  auto over_tokens = [&](const void* At, int M, const void* Bt, int rows, int ksplit, float scale,
+                         const GemmArgs::Out3 (&outs)[3]) {
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A = At; g.lda = TP; g.M = M;
+    g.Bsrc = Bt; g.ldb = TP; g.K = (int)TP;
+    g.Bsz = 1; g.N = rows; g.Npad = rows; g.src_padded = 1;
+    g.epi = 3; g.ksplit = ksplit; g.part = ws.part; g.out_scale = scale;
+    for (int u = 0; u < 3; ++u) g.out3[u] = outs[u];
+    return launch_gemm(f.dtype, g, 64, s);
+  };
+  {
+    const GemmArgs::Out3 o[3] = {{gr->dU2, 0, f.r2, f.r2},
+                                 {gr->dU3, c->R2, c->R2 + f.r3, f.r3},
+                                 {f.shared_kv ? nullptr : gr->dUt3, c->R2 + c->D, c->R2 + c->D + f.rt3, f.rt3}};
+    if (over_tokens(ws.Xt, f.d_model, ws.dLat_t, LW, ws.ks_w, 1.f, o) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("grad_u2_u3_ut3");
+  }
+  {
+    const GemmArgs::Out3 o[3] = {{gr->dUt2, 0, f.rt2, f.rt2}, {nullptr, 0, 0, 0}, {nullptr, 0, 0, 0}};
+    if (over_tokens(ws.dYt, f.d_model, ws.Zt, c->RT2, ws.ks_u, 1.f, o) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("grad_ut2");
+  }
+  {
+    const GemmArgs::Out3 o[3] = {{ws.dG, 0, nHD, nHD}, {nullptr, 0, 0, 0}, {nullptr, 0, 0, 0}};
+    if (over_tokens(ws.Qlat_t, c->R2, ws.dQt, nHD, ws.ks_g, 1.f, o) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("grad_core_mixed");
+  }
+  {
+    const GemmArgs::Out3 o[3] = {{ws.dGt, 0, nHD, nHD}, {nullptr, 0, 0, 0}, {nullptr, 0, 0, 0}};
+    if (over_tokens(ws.dZt, c->RT2, ws.Ot, nHD, ws.ks_g, 1.f, o) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("grad_core_mixed_post");
+  }
+
+  // ---- G_i = sum_a U1[i,a] C[a]: gradients of the core and of the head factor ----------------------------------
+  {
+    CoreGradArgs k;
+    std::memset(&k, 0, sizeof(k));
+    k.dG = ws.dG; k.D = c->D; k.nH = f.n_heads; k.C = w->C; k.U1 = w->U1; k.r1 = f.r1; k.r2 = f.r2; k.r3 = f.r3;
+    k.scale = (float)(1.0 / std::sqrt((double)f.d_head)); k.dC = gr->dC; k.dU1 = gr->dU1;
+    if (launch_core_grad(f.dtype, k, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    k.dG = ws.dGt; k.C = w->Ct; k.U1 = w->Ut1; k.r1 = f.rt1; k.r2 = f.rt2; k.r3 = f.rt3;
+    k.scale = 1.f; k.dC = gr->dCt; k.dU1 = gr->dUt1;
+    if (launch_core_grad(f.dtype, k, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("grad_core_and_head_factor");
+  }
   return TUCKER_ATTN_OK;
 }
 

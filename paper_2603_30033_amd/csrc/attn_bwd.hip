@@ -1,0 +1,532 @@
+// Backward pass of the fused prefill attention (the paper trains the layer, Section
+// "Experiments", and its timing tables carry a backward column; the gradient itself is the
+// derivative of Definition "Latent RoPE for Tucker Attention" followed by softmax attention over
+// the shared latent keys and values).  Flash-style: no N x N matrix is kept; probabilities are
+// recomputed from the saved log-sum-exp.
+//
+// With P_i = softmax(S_i), S_i = Q_i K^T (Q_i the rotated, scaled per-head query; K the rotated
+// latent keys), O_i = P_i V, and upstream dO_i = dZ G~_i:
+//     delta_i = rowsum(dO_i * O_i)          dP_i = dO_i V^T        dS_i = P_i * (dP_i - delta_i)
+//     dQ_i = dS_i K                         dK = sum_i dS_i^T Q_i  dV = sum_i P_i^T dO_i
+// Two kernels, neither with atomics:
+//   bwd_dq   one wave = 32 queries of one head, walks the key tiles like the forward kernel:
+//            builds Q_i and dO_i in a prologue from the latent query and dZ (and leaves copies of
+//            both, plain and transposed, for the second kernel), accumulates dQ_i, removes the
+//            rotation and stores it (plain for the latent-query gradient, transposed for the
+//            gradient of the core).
+//   bwd_dkv  one wave = 32 keys kept in registers as operands, walks (head, query block) pairs
+//            staged in LDS and accumulates dK^T and dV^T; heads are split into groups over
+//            workgroups, each writing a partial sum that kv_reduce adds up (and un-rotates).
+// Products are computed in the orientation that keeps the contraction index inside a lane (see
+// the fragment model in common.h): bwd_dq keeps queries as MFMA columns, bwd_dkv keeps keys.
+#include "common.h"
+#include "params.h"
+
+namespace ta {
+
+namespace {
+
+constexpr float kLn2 = 0.6931471805599453f;
+
+// acc[cb] = (32 rows c of core block cb) x (this wave's 32 tokens): sum_b G[c][b] xrow[token][b].
+// G: one head's fragment-major blocks [cb][bb]; xrow: this lane's token row + 16*h.
+template <typename T, int CB>
+__device__ __forceinline__ void core_product(f32x16 (&acc)[CB], const T* G, const T* xrow, int nbb, int lane) {
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[cb][e] = 0.f;
+  for (int bb = 0; bb < nbb; ++bb) {
+    const Frag<T> x = load_frag<T>(xrow + bb * 32);
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      const Frag<T> g = load_frag_major<T>(G + (long)(cb * nbb + bb) * kFragBlockElems, lane);
+      mma32(acc[cb], g, x);
+    }
+  }
+}
+
+// rotate (sign = +1) or un-rotate (sign = -1) the channel pairs of accumulator blocks whose column
+// (lane) sits at table position pos
+template <int CB>
+__device__ __forceinline__ void rotate_blocks(f32x16 (&a)[CB], const float4* rope, int rope_ld, int pos, int h,
+                                              float sign) {
+  const f32x4* tab = reinterpret_cast<const f32x4*>(rope) + (long)h * rope_ld + pos;
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) {
+    f32x4 cs[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) cs[q] = tab[(long)(cb * 8 + 2 * q) * rope_ld];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; e += 2) {
+        const float x0 = a[cb][4 * q + e], x1 = a[cb][4 * q + e + 1];
+        const float c = cs[q][e], s = sign * cs[q][e + 1];
+        a[cb][4 * q + e] = x0 * c - x1 * s;
+        a[cb][4 * q + e + 1] = x0 * s + x1 * c;
+      }
+  }
+}
+
+// element e of a fragment (same index as the accumulator register it came from)
+__device__ __forceinline__ float frag_elem(const Frag<float>& f, int e) { return f.v[e / 4][e % 4]; }
+__device__ __forceinline__ float frag_elem(const Frag<bf16>& f, int e) { return (float)f.v[e / 8][e % 8]; }
+
+}  // namespace
+
+// ---- dQ ----------------------------------------------------------------------------------------------
+template <typename T, int D, int BC> struct DqLds {
+  static constexpr int kRow = D + 16 / sizeof(T);               // K / V tile rows
+  static constexpr int kTRow = BC + 16 / sizeof(T);             // K^T tile rows
+  static constexpr int kKElems = BC * kRow;
+  static constexpr int kTElems = D * kTRow;
+  static constexpr int kStage = 2 * kKElems + kTElems;
+  static constexpr size_t kBytes = 2ul * kStage * sizeof(T);
+};
+
+template <typename T, int D, int BC>
+__global__ __launch_bounds__(256) void bwd_dq_kernel(BwdArgs p) {
+  constexpr int CB = D / 32, NB = BC / 32, HW = 4, TQ = 32, NT = 256;
+  constexpr int CE = 16 / sizeof(T);
+  using L = DqLds<T, D, BC>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* smem = reinterpret_cast<T*>(smem_raw);
+
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int h = lane / 32, lr = lane % 32;
+  const int n_qtiles = p.Npad / TQ;
+  const int qt = n_qtiles - 1 - blockIdx.y;                     // heavy (late causal) tiles first
+  const int n_hg = (p.nH + HW - 1) / HW;
+  const int b = blockIdx.x / n_hg;
+  const int head_raw = (blockIdx.x % n_hg) * HW + wave;
+  const bool head_ok = head_raw < p.nH;
+  const int head = head_ok ? head_raw : p.nH - 1;
+  const int t0 = qt * TQ;
+  const int m = t0 + lr;                                        // this lane's query, < Npad
+  const long tok_base = (long)b * p.Npad;
+  const long TP = (long)p.Bsz * p.Npad;
+
+  // staging of one key tile: K rows, V rows, K^T columns
+  constexpr int RCH = BC * D / CE;                              // chunks of a row tile (and of the transposed one)
+  constexpr int PT = RCH / NT;
+  static_assert(RCH % NT == 0, "tile must fill all threads");
+  constexpr int RCPR = D / CE, TCPR = BC / CE;
+  const T* Kg = static_cast<const T*>(p.Kr) + tok_base * D;
+  const T* Vg = static_cast<const T*>(p.Vr) + tok_base * D;
+  const T* Tg = static_cast<const T*>(p.Krt) + (long)b * D * p.Npad;
+  u32x4 kreg[PT], vreg[PT], treg[PT];
+  auto g_load = [&](int tile) {
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int ci = threadIdx.x + i * NT;
+      const int row = ci / RCPR, cc = ci % RCPR;
+      kreg[i] = *reinterpret_cast<const u32x4*>(Kg + (long)(tile * BC + row) * D + cc * CE);
+      vreg[i] = *reinterpret_cast<const u32x4*>(Vg + (long)(tile * BC + row) * D + cc * CE);
+      const int trow = ci / TCPR, tc = ci % TCPR;
+      treg[i] = *reinterpret_cast<const u32x4*>(Tg + (long)trow * p.Npad + tile * BC + tc * CE);
+    }
+  };
+  auto s_store = [&](int stage) {
+    T* ks = smem + (long)stage * L::kStage;
+    T* vs = ks + L::kKElems;
+    T* ts = vs + L::kKElems;
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int ci = threadIdx.x + i * NT;
+      const int row = ci / RCPR, cc = ci % RCPR;
+      *reinterpret_cast<u32x4*>(ks + row * L::kRow + cc * CE) = kreg[i];
+      *reinterpret_cast<u32x4*>(vs + row * L::kRow + cc * CE) = vreg[i];
+      const int trow = ci / TCPR, tc = ci % TCPR;
+      *reinterpret_cast<u32x4*>(ts + trow * L::kTRow + tc * CE) = treg[i];
+    }
+  };
+
+  g_load(0);
+
+  // ---- prologue: Q_i^T and dO_i^T of this wave's 32 tokens, delta, copies for the dK/dV kernel ----
+  Frag<T> qf[CB], dof[CB];
+  float delta, lse;
+  {
+    f32x16 qa[CB], da[CB];
+    const T* Gt = static_cast<const T*>(p.Gt) + (long)head * D * p.R2;
+    const T* Ql = static_cast<const T*>(p.Qlat) + (tok_base + m) * p.R2 + 16 * h;
+    core_product<T, CB>(qa, Gt, Ql, p.R2 / 32, lane);
+    if (p.rope != nullptr) rotate_blocks<CB>(qa, p.rope, p.rope_ld, p.pos0 + min(m, p.N - 1), h, 1.f);
+    const T* Gtt = static_cast<const T*>(p.Gtil_t) + (long)head * D * p.RT2;
+    const T* dZ = static_cast<const T*>(p.dZ) + (tok_base + m) * p.RT2 + 16 * h;
+    core_product<T, CB>(da, Gtt, dZ, p.RT2 / 32, lane);
+    const T* Orow = static_cast<const T*>(p.O) + ((tok_base + m) * p.nH + head) * D + 16 * h;
+    float dsum = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      qf[cb] = to_frag<T>(qa[cb]);
+      dof[cb] = to_frag<T>(da[cb]);
+      const Frag<T> of = load_frag<T>(Orow + cb * 32);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dsum += da[cb][e] * frag_elem(of, e);
+    }
+    delta = halves_sum(dsum);
+    lse = p.lse[((long)b * p.nH + head) * p.Npad + m];            // +inf for padding tokens
+    if (head_ok) {
+      if (h == 0) p.delta[((long)b * p.nH + head) * p.Npad + m] = delta;
+      T* Qr = static_cast<T*>(p.Qr) + ((tok_base + m) * p.nH + head) * D + 16 * h;
+      T* dOr = static_cast<T*>(p.dO) + ((tok_base + m) * p.nH + head) * D + 16 * h;
+      const long toff = (((long)b * p.nH + head) * D) * p.Npad + (m & ~31) + acc_pos(m & 31);
+      T* Qt = static_cast<T*>(p.Qt) + toff;
+      T* dOt = static_cast<T*>(p.dOt) + toff;
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) {
+        store_frag<T>(Qr + cb * 32, qf[cb]);
+        store_frag<T>(dOr + cb * 32, dof[cb]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const long c = cb * 32 + 8 * q + 4 * h + e;
+            store1(Qt + c * p.Npad, qa[cb][4 * q + e]);
+            store1(dOt + c * p.Npad, da[cb][4 * q + e]);
+          }
+      }
+    }
+  }
+
+  // ---- key tiles ------------------------------------------------------------------------------------
+  f32x16 dq[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dq[cb][e] = 0.f;
+  const int kv_end = p.causal ? min(p.N, t0 + TQ) : p.N;
+  const int n_tiles = (kv_end + BC - 1) / BC;
+  const int last = n_tiles - 1;
+  s_store(0);
+  __syncthreads();
+  for (int t = 0; t < n_tiles; ++t) {
+    g_load(min(t + 1, last));
+    const T* st = smem + (long)(t & 1) * L::kStage;
+    const T* kbase = st + lr * L::kRow + 16 * h;
+    const T* vbase = kbase + L::kKElems;
+    const T* tbase = st + 2 * L::kKElems + lr * L::kTRow + 16 * h;
+    f32x16 s[NB], dp[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { s[nb][e] = 0.f; dp[nb][e] = 0.f; }
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) mma32(s[nb], load_frag<T>(kbase + nb * 32 * L::kRow + cb * 32), qf[cb]);
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) mma32(dp[nb], load_frag<T>(vbase + nb * 32 * L::kRow + cb * 32), dof[cb]);
+    }
+    const int n0 = t * BC;
+    const int lim = p.causal ? min(m, p.N - 1) : p.N - 1;       // last visible key
+    Frag<T> dsf[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      f32x16 ds;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int n = n0 + nb * 32 + 8 * (e / 4) + 4 * h + (e % 4);
+        const float pr = n > lim ? 0.f : fast_exp2(s[nb][e] - lse);
+        ds[e] = pr * (dp[nb][e] - delta);
+      }
+      dsf[nb] = to_frag<T>(ds);
+    }
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) mma32(dq[cb], load_frag<T>(tbase + cb * 32 * L::kTRow + nb * 32), dsf[nb]);
+    s_store((t + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: remove the rotation, store plain and transposed -----------------------------------
+  if (p.rope != nullptr) rotate_blocks<CB>(dq, p.rope, p.rope_ld, p.pos0 + min(m, p.N - 1), h, -1.f);
+  if (head_ok) {
+    T* dQ = static_cast<T*>(p.dQ) + ((tok_base + m) * p.nH + head) * D + 16 * h;
+    T* dQt = static_cast<T*>(p.dQt) + ((long)head * D) * TP + tok_base + m;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      store_frag<T>(dQ + cb * 32, to_frag<T>(dq[cb]));
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) store1(dQt + (long)(cb * 32 + 8 * q + 4 * h + e) * TP, dq[cb][4 * q + e]);
+    }
+  }
+}
+
+// ---- dK, dV ------------------------------------------------------------------------------------------
+template <typename T, int D, int TQ> struct DkvLds {
+  static constexpr int kRow = D + 16 / sizeof(T);               // Q / dO rows
+  static constexpr int kTRow = TQ + 16 / sizeof(T);             // Q^T / dO^T rows
+  static constexpr int kRElems = TQ * kRow;
+  static constexpr int kTElems = D * kTRow;
+  static constexpr int kStageElems = 2 * kRElems + 2 * kTElems;
+  static constexpr size_t kStageBytes = kStageElems * sizeof(T) + 2ul * TQ * sizeof(float);
+  static constexpr size_t kBytes = 2ul * kStageBytes;
+};
+
+template <typename T, int D, int TQ>
+__global__ __launch_bounds__(256) void bwd_dkv_kernel(BwdArgs p) {
+  constexpr int CB = D / 32, QBN = TQ / 32, KT = 128, NT = 256;
+  constexpr int CE = 16 / sizeof(T);
+  using L = DkvLds<T, D, TQ>;
+  static_assert(L::kStageBytes % 16 == 0, "stages stay 16-byte aligned");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int h = lane / 32, lr = lane % 32;
+  const int b = blockIdx.x / p.n_hg, hg = blockIdx.x % p.n_hg;
+  const int key0 = blockIdx.y * KT + 32 * wave;                 // first key of this wave
+  const int nk = key0 + lr;                                     // this lane's key
+  const bool key_ok = nk < p.Npad;
+  const long tok_base = (long)b * p.Npad;
+  const long TP = (long)p.Bsz * p.Npad;
+
+  // this wave's keys and values as MFMA column operands, for the whole kernel
+  Frag<T> kf[CB], vf[CB];
+  {
+    const long row = tok_base + (key_ok ? nk : 0);
+    const T* Kg = static_cast<const T*>(p.Kr) + row * D + 16 * h;
+    const T* Vg = static_cast<const T*>(p.Vr) + row * D + 16 * h;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      kf[cb] = key_ok ? load_frag<T>(Kg + cb * 32) : zero_frag<T>();
+      vf[cb] = key_ok ? load_frag<T>(Vg + cb * 32) : zero_frag<T>();
+    }
+  }
+  f32x16 dk[CB], dv[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { dk[cb][e] = 0.f; dv[cb][e] = 0.f; }
+
+  // (head, query block) pairs of this workgroup
+  const int head0 = hg * p.hpg;
+  const int n_heads = min(p.hpg, p.nH - head0);
+  const int qb_first = p.causal ? (blockIdx.y * KT) / TQ : 0;
+  const int n_qb = p.Npad / TQ - qb_first;                      // >= 1: the grid covers Npad
+  const int n_it = n_heads * n_qb;
+
+  constexpr int RCH = TQ * D / CE, PT = (RCH + NT - 1) / NT;    // chunks per tensor, per thread
+  static_assert(RCH % NT == 0, "tile must fill all threads");
+  constexpr int RCPR = D / CE, TCPR = TQ / CE;
+  u32x4 qreg[PT], oreg[PT], qtreg[PT], otreg[PT];
+  float statreg = 0.f;
+  auto g_load = [&](int it) {
+    const int head = head0 + it / n_qb, q0 = (qb_first + it % n_qb) * TQ;
+    const T* Qg = static_cast<const T*>(p.Qr) + ((tok_base + q0) * p.nH + head) * D;
+    const T* Og = static_cast<const T*>(p.dO) + ((tok_base + q0) * p.nH + head) * D;
+    const long toff = (((long)b * p.nH + head) * D) * p.Npad + q0;
+    const T* Qtg = static_cast<const T*>(p.Qt) + toff;
+    const T* Otg = static_cast<const T*>(p.dOt) + toff;
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int ci = threadIdx.x + i * NT;
+      const int row = ci / RCPR, cc = ci % RCPR;
+      qreg[i] = *reinterpret_cast<const u32x4*>(Qg + (long)row * p.nH * D + cc * CE);
+      oreg[i] = *reinterpret_cast<const u32x4*>(Og + (long)row * p.nH * D + cc * CE);
+      const int trow = ci / TCPR, tc = ci % TCPR;
+      qtreg[i] = *reinterpret_cast<const u32x4*>(Qtg + (long)trow * p.Npad + tc * CE);
+      otreg[i] = *reinterpret_cast<const u32x4*>(Otg + (long)trow * p.Npad + tc * CE);
+    }
+    // threads 0..TQ-1 fetch the log-sum-exp of the block's queries, threads 128.. their delta
+    const long so = ((long)b * p.nH + head) * p.Npad + q0;
+    if (threadIdx.x < TQ) statreg = p.lse[so + threadIdx.x];
+    else if (threadIdx.x >= 128 && threadIdx.x < 128 + TQ) statreg = p.delta[so + threadIdx.x - 128];
+  };
+  auto s_store = [&](int stage) {
+    unsigned char* sb = smem_raw + (size_t)stage * L::kStageBytes;
+    T* qs = reinterpret_cast<T*>(sb);
+    T* os = qs + L::kRElems;
+    T* qts = os + L::kRElems;
+    T* ots = qts + L::kTElems;
+    float* stat = reinterpret_cast<float*>(ots + L::kTElems);
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int ci = threadIdx.x + i * NT;
+      const int row = ci / RCPR, cc = ci % RCPR;
+      *reinterpret_cast<u32x4*>(qs + row * L::kRow + cc * CE) = qreg[i];
+      *reinterpret_cast<u32x4*>(os + row * L::kRow + cc * CE) = oreg[i];
+      const int trow = ci / TCPR, tc = ci % TCPR;
+      *reinterpret_cast<u32x4*>(qts + trow * L::kTRow + tc * CE) = qtreg[i];
+      *reinterpret_cast<u32x4*>(ots + trow * L::kTRow + tc * CE) = otreg[i];
+    }
+    if (threadIdx.x < TQ) stat[threadIdx.x] = statreg;
+    else if (threadIdx.x >= 128 && threadIdx.x < 128 + TQ) stat[TQ + threadIdx.x - 128] = statreg;
+  };
+
+  g_load(0);
+  s_store(0);
+  __syncthreads();
+  for (int it = 0; it < n_it; ++it) {
+    g_load(min(it + 1, n_it - 1));
+    const unsigned char* sb = smem_raw + (size_t)(it & 1) * L::kStageBytes;
+    const T* qs = reinterpret_cast<const T*>(sb);
+    const T* os = qs + L::kRElems;
+    const T* qts = os + L::kRElems;
+    const T* ots = qts + L::kTElems;
+    const float* stat = reinterpret_cast<const float*>(ots + L::kTElems);
+    const int q0 = (qb_first + it % n_qb) * TQ;
+#pragma unroll
+    for (int qb = 0; qb < QBN; ++qb) {
+      const int qfirst = q0 + 32 * qb;
+      // all 32 keys of the wave lie after all 32 queries of the block: nothing to do
+      if (p.causal && key0 > qfirst + 31) continue;
+      f32x16 s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+      const T* qrow = qs + (qb * 32 + lr) * L::kRow + 16 * h;
+      const T* orow = os + (qb * 32 + lr) * L::kRow + 16 * h;
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) mma32(s, load_frag<T>(qrow + cb * 32), kf[cb]);
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) mma32(dp, load_frag<T>(orow + cb * 32), vf[cb]);
+      f32x16 pr, ds;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + qb * 32 + 8 * q + 4 * h);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + TQ + qb * 32 + 8 * q + 4 * h);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int mq = qfirst + 8 * q + 4 * h + e;            // query of this register
+          const bool masked = nk >= p.N || (p.causal && nk > mq);
+          const float v = masked ? 0.f : fast_exp2(s[4 * q + e] - l4[e]);
+          pr[4 * q + e] = v;
+          ds[4 * q + e] = v * (dp[4 * q + e] - d4[e]);
+        }
+      }
+      const Frag<T> pf = to_frag<T>(pr), dsf = to_frag<T>(ds);
+      const T* otrow = ots + lr * L::kTRow + qb * 32 + 16 * h;
+      const T* qtrow = qts + lr * L::kTRow + qb * 32 + 16 * h;
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) mma32(dv[cb], load_frag<T>(otrow + cb * 32 * L::kTRow), pf);
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) mma32(dk[cb], load_frag<T>(qtrow + cb * 32 * L::kTRow), dsf);
+    }
+    s_store((it + 1) & 1);
+    __syncthreads();
+  }
+
+  if (key_ok) {
+    float* dK = p.dKp + ((long)hg * TP + tok_base + nk) * D + 4 * h;
+    float* dV = p.dVp + ((long)hg * TP + tok_base + nk) * D + 4 * h;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        store4(dK + cb * 32 + 8 * q, dk[cb][4 * q], dk[cb][4 * q + 1], dk[cb][4 * q + 2], dk[cb][4 * q + 3]);
+        store4(dV + cb * 32 + 8 * q, dv[cb][4 * q], dv[cb][4 * q + 1], dv[cb][4 * q + 2], dv[cb][4 * q + 3]);
+      }
+  }
+}
+
+// ---- sum of the head-group partials, rotation removed from the key part -----------------------------
+// The scores carry a factor log2(e) (the per-head query is pre-scaled so that the softmax runs on
+// exp2), so the key gradient formed from those queries is multiplied by ln 2 here.
+template <typename T>
+__global__ __launch_bounds__(256) void kv_reduce_kernel(KvReduceArgs a) {
+  const long TP = (long)a.Bsz * a.Npad;
+  const int quads = a.D / 4;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= TP * quads) return;
+  const long tp = idx / quads;
+  const int k = (int)(idx % quads);
+  const int n = (int)(tp % a.Npad);
+  f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
+  for (int g = 0; g < a.n_hg; ++g) {
+    const long off = ((long)g * TP + tp) * a.D + 4 * k;
+    const f32x4 x = *reinterpret_cast<const f32x4*>(a.dKp + off);
+    const f32x4 y = *reinterpret_cast<const f32x4*>(a.dVp + off);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { sk[e] += x[e]; sv[e] += y[e]; }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) sk[e] *= kLn2;
+  if (a.rope != nullptr && n < a.N) {
+    const f32x4 cs = reinterpret_cast<const f32x4*>(a.rope)[(long)k * a.rope_ld + a.pos0 + n];
+#pragma unroll
+    for (int e = 0; e < 4; e += 2) {
+      const float x0 = sk[e], x1 = sk[e + 1];
+      sk[e] = x0 * cs[e] + x1 * cs[e + 1];
+      sk[e + 1] = -x0 * cs[e + 1] + x1 * cs[e];
+    }
+  }
+  T* row = static_cast<T*>(a.dLat) + tp * a.ld;
+  if (a.shared_kv) {
+    store4(row + a.colK + 4 * k, sk[0] + sv[0], sk[1] + sv[1], sk[2] + sv[2], sk[3] + sv[3]);
+  } else {
+    store4(row + a.colK + 4 * k, sk[0], sk[1], sk[2], sk[3]);
+    store4(row + a.colV + 4 * k, sv[0], sv[1], sv[2], sv[3]);
+  }
+}
+
+// ---- launchers ---------------------------------------------------------------------------------------
+template <typename T, int D, int BC>
+static hipError_t dq_one(const BwdArgs& a, hipStream_t s) {
+  dim3 grid(((a.nH + 3) / 4) * a.Bsz, a.Npad / 32);
+  const size_t smem = DqLds<T, D, BC>::kBytes;
+  auto kern = bwd_dq_kernel<T, D, BC>;
+  static LdsOnce lds_once;
+  if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
+  hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_dq(int dtype, const BwdArgs& a, hipStream_t s) {
+  if (dtype == 0) {
+    switch (a.D) {
+      case 32: return dq_one<float, 32, 32>(a, s);
+      case 64: return dq_one<float, 64, 32>(a, s);
+      case 128: return dq_one<float, 128, 32>(a, s);
+    }
+  } else {
+    switch (a.D) {
+      case 32: return dq_one<bf16, 32, 64>(a, s);
+      case 64: return dq_one<bf16, 64, 64>(a, s);
+      case 128: return dq_one<bf16, 128, 64>(a, s);
+    }
+  }
+  return hipErrorInvalidValue;
+}
+
+template <typename T, int D, int TQ>
+static hipError_t dkv_one(const BwdArgs& a, hipStream_t s) {
+  dim3 grid(a.n_hg * a.Bsz, (a.Npad + 127) / 128);
+  const size_t smem = DkvLds<T, D, TQ>::kBytes;
+  auto kern = bwd_dkv_kernel<T, D, TQ>;
+  static LdsOnce lds_once;
+  if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
+  hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_dkv(int dtype, const BwdArgs& a, hipStream_t s) {
+  if (dtype == 0) {
+    switch (a.D) {
+      case 32: return dkv_one<float, 32, 32>(a, s);
+      case 64: return dkv_one<float, 64, 32>(a, s);
+      case 128: return dkv_one<float, 128, 32>(a, s);
+    }
+  } else {
+    switch (a.D) {
+      case 32: return dkv_one<bf16, 32, 64>(a, s);
+      case 64: return dkv_one<bf16, 64, 32>(a, s);
+      case 128: return dkv_one<bf16, 128, 32>(a, s);
+    }
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_kv_reduce(int dtype, const KvReduceArgs& a, hipStream_t s) {
+  const long total = (long)a.Bsz * a.Npad * (a.D / 4);
+  const int blocks = (int)((total + 255) / 256);
+  if (dtype == 0)
+    hipLaunchKernelGGL(kv_reduce_kernel<float>, dim3(blocks), dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL(kv_reduce_kernel<bf16>, dim3(blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace ta

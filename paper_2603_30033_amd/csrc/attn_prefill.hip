@@ -346,22 +346,24 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
   }
 
   // ---- epilogue: normalise, store O[tok][head][c] (acc order in c) -------------------------
+  // Rows of padding tokens (N <= m < Npad) are written as zeros, and their log-sum-exp as +inf,
+  // so that a pass over all padded rows (the backward kernels) sees no undefined values.
   if (head_ok) {
     T* O = static_cast<T*>(p.O);
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      const int m = tw + 32 * qb + lr;
+      const int m = tw + 32 * qb + lr;                          // < Npad
       const float l_tot = halves_sum(l_run[qb]);
-      const float inv = 1.f / l_tot;
-      if (m < p.N) {
+      const float inv = m < p.N ? 1.f / l_tot : 0.f;
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-          f32x16 o = oacc[qb][cb];
+      for (int cb = 0; cb < CB; ++cb) {
+        f32x16 o = oacc[qb][cb];
 #pragma unroll
-          for (int e = 0; e < 16; ++e) o[e] *= inv;
-          store_frag<T>(O + ((tok_base + m) * p.nH + head) * D + cb * 32 + 16 * h, to_frag<T>(o));
-        }
+        for (int e = 0; e < 16; ++e) o[e] = m < p.N ? o[e] * inv : 0.f;
+        store_frag<T>(O + ((tok_base + m) * p.nH + head) * D + cb * 32 + 16 * h, to_frag<T>(o));
       }
+      if (p.lse != nullptr && h == 0)
+        p.lse[((long)b * p.nH + head) * p.Npad + m] = m < p.N ? m_ref[qb] + log2f(l_tot) : INFINITY;
     }
   }
 }

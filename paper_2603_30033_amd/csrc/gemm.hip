@@ -108,6 +108,7 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, in
 #pragma unroll
             for (int e = 0; e < 4; ++e) store1(base + (long)(c0 + 8 * q + 4 * h + e) * g.Npad, acc[4 * q + e]);
         }
+        if (g.Vr != nullptr) store_frag<T>(static_cast<T*>(g.Vr) + (long)tp * g.D + c0 + 16 * h, to_frag<T>(acc));
         if (g.Kcache != nullptr && valid) {
           T* row = static_cast<T*>(g.Kcache) + ((long)b * g.Lmax + pos) * g.r3;
 #pragma unroll
@@ -142,6 +143,13 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, in
         T* dst = static_cast<T*>(g.Kr) + (long)tp * g.D + c0 + 16 * h;
         store_frag<T>(dst, to_frag<T>(acc));
       }
+      if (g.Krt != nullptr) {
+        T* base = static_cast<T*>(g.Krt) + (long)b * g.D * g.Npad + (n & ~31) + acc_pos(n & 31);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) store1(base + (long)(c0 + 8 * q + 4 * h + e) * g.Npad, acc[4 * q + e]);
+      }
       if (g.Kcache != nullptr && valid && !g.shared_kv) {
         T* row = static_cast<T*>(g.Kcache) + ((long)b * g.Lmax + pos) * g.r3;
 #pragma unroll
@@ -157,6 +165,7 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, in
       }
     } else {                                                    // ---- V
       const int c0 = m0 - g.R2 - g.D;
+      if (g.Vr != nullptr) store_frag<T>(static_cast<T*>(g.Vr) + (long)tp * g.D + c0 + 16 * h, to_frag<T>(acc));
       if (g.Vt != nullptr) {
         // Vt[b][c][n], n stored at its acc-order position inside its 32-block
         T* base = static_cast<T*>(g.Vt) + (long)b * g.D * g.Npad + (n & ~31) + acc_pos(n & 31);
@@ -188,6 +197,19 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, in
     for (int q = 0; q < 4; ++q) {
       int c = m0 + 8 * q + 4 * h;
       if (c < g.M) store4(row + c, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    }
+  } else if (g.epi == 3) {                                      // ---- fp32 matrix, column ranges routed
+#pragma unroll
+    for (int u = 0; u < 3; ++u) {
+      const GemmArgs::Out3& o = g.out3[u];
+      if (o.ptr == nullptr || tp < o.n0 || tp >= o.n1) continue;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int m = m0 + 8 * q + 4 * h + e;
+          if (m < g.M) o.ptr[(long)m * o.ld + (tp - o.n0)] = g.out_scale * acc[4 * q + e];
+        }
     }
   } else {                                                      // ---- Y, caller's [B][N][d]
     if (!valid) return;

@@ -46,11 +46,13 @@ struct GemmArgs {
   int Bsz, N, Npad;
   int src_padded;       // 1: Bsrc rows are indexed by tp; 0: by b*N+n (caller's X)
   // epilogue outputs
-  int epi;              // 0 = projection, 1 = latent merge Z, 2 = output Y
+  int epi;              // 0 = projection, 1 = latent merge Z, 2 = output Y, 3 = fp32 matrix (gradients)
   // projection
   void* Qlat; int R2;           // [TP][R2] acc order
   void* Kr;   int D;            // [TP][D]  acc order, rotated
   void* Vt;                     // [B][D][Npad], n in acc order within 32-blocks; null in decode
+  void* Vr;                     // nullable [TP][D] acc order: value rows (for the backward pass)
+  void* Krt;                    // nullable [B][D][Npad] like Vt: rotated keys, transposed (backward pass)
   void* Kcache; void* Vcache;   // nullable [B][Lmax][r3]/[B][Lmax][rt3], natural order
   int Lmax, r3, rt3;
   // rotation table or null: [D/4][rope_ld positions] entries (cos, sin, cos, sin) of the channel
@@ -69,6 +71,10 @@ struct GemmArgs {
   // epilogue
   int ksplit;
   float* part;
+  // epi 3: out_scale * acc[m][n] as fp32; column range [n0, n1) of the product goes to
+  // ptr[m * ld + (n - n0)] (up to three destinations; ptr null = unused)
+  struct Out3 { float* ptr; int n0, n1; long ld; } out3[3];
+  float out_scale;
 };
 
 // ---- prefill attention ---------------------------------------------------------------------
@@ -77,11 +83,67 @@ struct AttnArgs {
   const void* Gt;     // [nH] x fragment-major 32x32 blocks of Gt[i][c][b] = qscale * G_i[b][c], b in acc order
   const void* Kr;     // [TP][D]
   const void* Vt;     // [B][D][Npad]
-  void* O;            // [TP][nH][D] acc order in c, normalised
+  void* O;            // [TP][nH][D] acc order in c, normalised; rows of padding tokens are zero
+  float* lse;         // nullable [B][nH][Npad]: log2 of the softmax denominator (+inf for padding tokens)
   const float4* rope; // [D/4][rope_ld] as in GemmArgs, or null
   int rope_ld;
   int Bsz, N, Npad, nH, R2, r3, D;   // D = padded common width of K and V (32, 64 or 128)
   int causal, pos0;
+};
+
+// ---- backward pass of prefill attention ---------------------------------------------------------
+struct BwdArgs {
+  const void* Qlat;    // [TP][R2] acc order
+  const void* Gt;      // as AttnArgs
+  const void* dZ;      // [TP][RT2] natural order (rows of padding tokens zero)
+  const void* Gtil_t;  // [nH] x fragment-major blocks of G~t[i][c][b] = G~_i[b][c], b natural
+  const void* Kr;      // [TP][D] rotated keys, acc order in c
+  const void* Vr;      // [TP][D] values, acc order in c
+  const void* Krt;     // [B][D][Npad] rotated keys transposed, n acc order
+  const void* O;       // [TP][nH][D]
+  const float* lse;    // [B][nH][Npad]
+  float* delta;        // [B][nH][Npad]  sum_c dO O
+  void* Qr;            // [TP][nH][D] rotated, scaled per-head queries (acc order in c)
+  void* dO;            // [TP][nH][D] (acc order in c)
+  void* Qt;            // [B][nH][D][Npad] transposes of the two, n in acc order within 32-blocks
+  void* dOt;
+  void* dQ;            // [TP][nH][D] gradient of the unrotated per-head query / sqrt-free scale, acc order in c
+  void* dQt;           // [nH*D][TP] the same, c natural, tokens natural
+  float* dKp;          // [n_hg][TP][D] per-head-group partial gradients of the rotated keys / values
+  float* dVp;
+  const float4* rope;
+  int rope_ld;
+  int Bsz, N, Npad, nH, R2, RT2, D;
+  int causal, pos0;
+  int hpg, n_hg;       // heads per group and number of groups of the key/value gradient kernel
+};
+
+// dLat[tp][col0 + c] from the partial key/value gradients: keys un-rotated; with a shared latent
+// the value part is added to the key part
+struct KvReduceArgs {
+  const float* dKp; const float* dVp;
+  void* dLat; long ld; int colK, colV;
+  const float4* rope; int rope_ld;
+  int Bsz, N, Npad, D, n_hg, pos0, shared_kv;
+};
+
+// out[c][tp] = src[row(tp)][c] (zero where the token or the column does not exist)
+struct TransposeArgs {
+  const void* src; long ld;
+  int cols;            // source columns to move; output rows cols .. cols_pad-1 are zero filled
+  int cols_pad;
+  int Bsz, N, Npad, src_padded;
+  int unperm;          // 1: source columns are stored in acc order within 32-blocks; output rows natural
+  void* dst;           // [cols_pad][TP]
+};
+
+// dC[a][b][c] = scale * sum_i U1[i][a] dG[b][i*D + c];  dU1[i][a] = scale * sum_bc dG[b][i*D+c] C[a][b][c]
+struct CoreGradArgs {
+  const float* dG; int D, nH;
+  const void* C; const void* U1;
+  int r1, r2, r3;
+  float scale;
+  float* dC; float* dU1;
 };
 
 // ---- decode ------------------------------------------------------------------------------
@@ -126,6 +188,11 @@ bool out_proj_supported(int dtype, const GemmArgs& a);
 hipError_t launch_out_proj(int dtype, const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm(int dtype, const GemmArgs& a, int tile_n, hipStream_t s);
 hipError_t launch_attn_prefill(int dtype, const AttnArgs& a, hipStream_t s);
+hipError_t launch_bwd_dq(int dtype, const BwdArgs& a, hipStream_t s);
+hipError_t launch_bwd_dkv(int dtype, const BwdArgs& a, hipStream_t s);
+hipError_t launch_kv_reduce(int dtype, const KvReduceArgs& a, hipStream_t s);
+hipError_t launch_transpose(int dtype, const TransposeArgs& a, hipStream_t s);
+hipError_t launch_core_grad(int dtype, const CoreGradArgs& a, hipStream_t s);
 hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_merge(int dtype, const DecodeArgs& a, hipStream_t s);

@@ -67,6 +67,15 @@ class Layer:
         ta.tucker_attn_forward(self.ctx, self.weights, X, Y, pos0, Kc, Vc, ws)
         return Y
 
+    def backward(self, X: torch.Tensor, dY: torch.Tensor, pos0: int = 0):
+        """Returns (dX, dict of fp32 weight gradients)."""
+        B, N = X.shape[0], X.shape[1]
+        dX = torch.empty_like(X)
+        grads = {"d" + k: torch.empty(self.weights[k].shape, dtype=torch.float32, device="cuda") for k in self.weights}
+        ws = self.workspace(ta.tucker_attn_backward_workspace_bytes(self.ctx, B, N))
+        ta.tucker_attn_backward(self.ctx, self.weights, X, dY, dX, grads, pos0, ws)
+        return dX, grads
+
     def decode(self, x: torch.Tensor, Kc: torch.Tensor, Vc: Optional[torch.Tensor], kv_len, y=None) -> torch.Tensor:
         if y is None:
             y = torch.empty_like(x)
