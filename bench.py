@@ -58,6 +58,19 @@ def flops(w, N=None, B=None):
                 total=proj + qhat + attn + merge + out)
 
 
+def backward_flops(w):
+    """Algorithmic FLOPs of one backward: every product of the forward has two gradient products of the
+    same size, and the attention has five products per visible (query, key) pair (scores and dP are
+    recomputed once, then dQ, dK, dV) against the forward's two.  Re-running the forward, which this
+    library's backward does inside the call, is not counted."""
+    f = flops(w)
+    rt3 = w.ranks_post()[2]
+    pairs = w.N * (w.N + 1) // 2 if w.causal else w.N * w.N
+    attn = w.B * w.n_heads * pairs * (6 * w.r3 + 4 * rt3)
+    dense = 2 * (f["proj"] + f["qhat"] + f["merge"] + f["out"])
+    return dict(attn=attn, dense=dense, total=attn + dense)
+
+
 def mandatory_bytes(w):
     es = 2 if w.dtype == "bf16" else 4
     rt1, rt2, rt3 = w.ranks_post()
@@ -68,7 +81,7 @@ def mandatory_bytes(w):
     return 2 * w.B * w.N * w.d_model * es + wts
 
 
-def cpu_baseline(w):
+def cpu_baseline(w, backward=False):
     """The oracle as it stands, timed on the host cores on a bounded sample of the workload."""
     import numpy as np
     from threadpoolctl import threadpool_info
@@ -88,6 +101,18 @@ def cpu_baseline(w):
         dt = time.perf_counter() - t0
         f = flops(ws)["total"]
         sample = f"decode step of {ws.B} of the {w.B} sequences at kv_len={w.kv_len} (cache given, as for the GPU)"
+    elif backward:
+        from oracle import tucker_backward as orb
+        n = min(w.N, 2048)
+        b = 1 if w.N >= 1024 else min(w.B, 8)
+        ws = wl.scaled(w, B=b, N=n)
+        inp = wl.make_inputs(ws)
+        dY = np.random.default_rng(1).standard_normal(inp["X"].shape).astype(np.float32)
+        t0 = time.perf_counter()
+        orb.backward(inp["X"], dY, wl.weights_of(inp), ws.d_head, ws.causal, ws.rope_base, shared_kv=ws.shared_kv)
+        dt = time.perf_counter() - t0
+        f = backward_flops(ws)["total"]
+        sample = f"full oracle backward of {b} sequence(s) of {n} tokens of the same layer shape"
     else:
         n = min(w.N, 4096)
         b = 1 if w.N >= 1024 else min(w.B, 16)
@@ -109,6 +134,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="llama7b_n4096")
+    ap.add_argument("--pass", dest="which", choices=["forward", "backward"], default="forward",
+                    help="backward: one step = one tucker_attn_backward call (prefill workloads only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also launch a plain device-to-device copy of this many MiB (three times), so that a "
@@ -133,6 +160,12 @@ def main():
     inp = wl.make_inputs(w)
     K, W = args.steps, args.warmup
     fl = flops(w)
+    backward = args.which == "backward"
+    if backward and w.mode == "decode":
+        log("a decode step has no backward pass")
+        sys.exit(2)
+    if backward:
+        fb = backward_flops(w)
 
     if args.copy_calibration_mib > 0:
         src = torch.randint(0, 255, (args.copy_calibration_mib << 20,), dtype=torch.uint8, device="cuda")
@@ -165,9 +198,19 @@ def main():
             X = to_device(inp["X"], w.dtype)
             Y = torch.empty_like(X)
             ws = layer.workspace(ta.tucker_attn_workspace_bytes(layer.ctx, w.B, w.N))
+            if backward:
+                dY = to_device(wl.round_to_storage(
+                    np.random.default_rng(w.seed + 1000).standard_normal(inp["X"].shape).astype(np.float32), w.dtype),
+                    w.dtype)
+                grads = {"d" + k: torch.empty(v.shape, dtype=torch.float32, device="cuda")
+                         for k, v in layer.weights.items()}
+                ws = layer.workspace(ta.tucker_attn_backward_workspace_bytes(layer.ctx, w.B, w.N))
 
-            def step():
-                ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, w.pos0, None, None, ws)
+                def step():
+                    ta.tucker_attn_backward(layer.ctx, layer.weights, X, dY, Y, grads, w.pos0, ws)
+            else:
+                def step():
+                    ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, w.pos0, None, None, ws)
             units = w.B * w.N
 
         for _ in range(W):
@@ -194,13 +237,23 @@ def main():
         ta.tucker_attn_profile_enable(layer.ctx, False)
         kern_ms = {n: acc[n] / K for n in order}
 
-    tflops = fl["total"] / (ms * 1e-3) / 1e12
+    total_flops = fb["total"] if backward else fl["total"]
+    tflops = total_flops / (ms * 1e-3) / 1e12
     log(f"{w.name}: {ms:.4f} ms/step, {tflops:.1f} TFLOP/s algorithmic, {units / (ms * 1e-3):.3e} tokens/s")
     for n in order:
         log(f"  {n:20s} {kern_ms[n] * 1e3:9.1f} us")
     log(f"  sum of kernels       {sum(kern_ms.values()) * 1e3:9.1f} us")
 
-    if w.mode == "decode":
+    if backward:
+        # the two attention-gradient kernels together, against the five products per visible pair
+        dom = "attention_bwd_dq+attention_bwd_dkv"
+        t_ms = kern_ms["attention_bwd_dq"] + kern_ms["attention_bwd_dkv"]
+        peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS
+        alg = fb["attn"] + 2 * fl["qhat"]
+        ach = alg / (t_ms * 1e-3) / 1e12
+        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                "frac": ach / peak, "traffic": None, "algorithmic_flops": alg, "avg_us": t_ms * 1e3}
+    elif w.mode == "decode":
         dom = "decode_attention"
         es = 2 if w.dtype == "bf16" else 4
         rt3 = w.ranks_post()[2]
@@ -218,7 +271,8 @@ def main():
                 "algorithmic_flops": fl["attn"] + fl["qhat"], "avg_us": kern_ms[dom] * 1e3}
 
     out = {
-        "metric": "tucker_attn_fwd_tflops" if w.mode != "decode" else "tucker_attn_decode_tflops",
+        "metric": ("tucker_attn_bwd_tflops" if backward else
+                   "tucker_attn_fwd_tflops" if w.mode != "decode" else "tucker_attn_decode_tflops"),
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "N": w.N if w.mode != "decode" else w.kv_len,
@@ -226,15 +280,16 @@ def main():
                    "ranks": [w.r1, w.r2, w.r3], "causal": w.causal, "rope_base": w.rope_base, "mode": w.mode,
                    "shared_kv": w.shared_kv},
         "tokens_per_s": units / (ms * 1e-3),
+        "pass": args.which,
         "pct_mfma_peak": 100.0 * tflops / (PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS),
         "hbm_gbs_mandatory": mandatory_bytes(w) / (ms * 1e-3) / 1e9,
-        "algorithmic_gflop": fl["total"] / 1e9,
+        "algorithmic_gflop": total_flops / 1e9,
         "kernel_us": {n: kern_ms[n] * 1e3 for n in order},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample ...")
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w, backward)
     print(json.dumps(out), flush=True)
 
 

@@ -14,9 +14,10 @@
 //            both, plain and transposed, for the second kernel), accumulates dQ_i, removes the
 //            rotation and stores it (plain for the latent-query gradient, transposed for the
 //            gradient of the core).
-//   bwd_dkv  one wave = 32 keys kept in registers as operands, walks (head, query block) pairs
-//            staged in LDS and accumulates dK^T and dV^T; heads are split into groups over
-//            workgroups, each writing a partial sum that kv_reduce adds up (and un-rotates).
+//   bwd_dkv  a pair of waves = 32 keys kept in registers as operands, walks (head, query block)
+//            pairs staged in LDS; one wave of the pair accumulates dV^T, the other dK^T; heads are
+//            split into groups over workgroups, each writing a partial sum that kv_reduce adds up
+//            (and un-rotates).
 // Products are computed in the orientation that keeps the contraction index inside a lane (see
 // the fragment model in common.h): bwd_dq keeps queries as MFMA columns, bwd_dkv keeps keys.
 #include "common.h"
@@ -85,9 +86,12 @@ template <typename T, int D, int BC> struct DqLds {
   static constexpr size_t kBytes = 2ul * kStage * sizeof(T);
 };
 
+// Workgroup = 8 waves = 4 heads x 2 blocks of 32 queries (waves w and w+4 share a SIMD); key tiles
+// of BC keys are staged once per workgroup and walked in 32-key halves, so that only one half's
+// scores live in registers at a time.
 template <typename T, int D, int BC>
-__global__ __launch_bounds__(256) void bwd_dq_kernel(BwdArgs p) {
-  constexpr int CB = D / 32, NB = BC / 32, HW = 4, TQ = 32, NT = 256;
+__global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs p) {
+  constexpr int CB = D / 32, NB = BC / 32, HW = 4, QW = 2, TQ = 32 * QW, NT = 64 * HW * QW;
   constexpr int CE = 16 / sizeof(T);
   using L = DqLds<T, D, BC>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -99,18 +103,19 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(BwdArgs p) {
   const int qt = n_qtiles - 1 - blockIdx.y;                     // heavy (late causal) tiles first
   const int n_hg = (p.nH + HW - 1) / HW;
   const int b = blockIdx.x / n_hg;
-  const int head_raw = (blockIdx.x % n_hg) * HW + wave;
+  const int head_raw = (blockIdx.x % n_hg) * HW + wave % HW;
   const bool head_ok = head_raw < p.nH;
   const int head = head_ok ? head_raw : p.nH - 1;
   const int t0 = qt * TQ;
-  const int m = t0 + lr;                                        // this lane's query, < Npad
+  const int tw = t0 + (wave / HW) * 32;                         // first query of this wave
+  const int m = tw + lr;                                        // this lane's query, < Npad
   const long tok_base = (long)b * p.Npad;
   const long TP = (long)p.Bsz * p.Npad;
 
   // staging of one key tile: K rows, V rows, K^T columns
   constexpr int RCH = BC * D / CE;                              // chunks of a row tile (and of the transposed one)
-  constexpr int PT = RCH / NT;
-  static_assert(RCH % NT == 0, "tile must fill all threads");
+  constexpr int PT = (RCH + NT - 1) / NT;
+  constexpr bool FULL = RCH % NT == 0;
   constexpr int RCPR = D / CE, TCPR = BC / CE;
   const T* Kg = static_cast<const T*>(p.Kr) + tok_base * D;
   const T* Vg = static_cast<const T*>(p.Vr) + tok_base * D;
@@ -120,6 +125,7 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(BwdArgs p) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int ci = threadIdx.x + i * NT;
+      if (!FULL && ci >= RCH) break;
       const int row = ci / RCPR, cc = ci % RCPR;
       kreg[i] = *reinterpret_cast<const u32x4*>(Kg + (long)(tile * BC + row) * D + cc * CE);
       vreg[i] = *reinterpret_cast<const u32x4*>(Vg + (long)(tile * BC + row) * D + cc * CE);
@@ -134,6 +140,7 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(BwdArgs p) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int ci = threadIdx.x + i * NT;
+      if (!FULL && ci >= RCH) break;
       const int row = ci / RCPR, cc = ci % RCPR;
       *reinterpret_cast<u32x4*>(ks + row * L::kRow + cc * CE) = kreg[i];
       *reinterpret_cast<u32x4*>(vs + row * L::kRow + cc * CE) = vreg[i];
@@ -146,7 +153,7 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(BwdArgs p) {
 
   // ---- prologue: Q_i^T and dO_i^T of this wave's 32 tokens, delta, copies for the dK/dV kernel ----
   Frag<T> qf[CB], dof[CB];
-  float delta, lse;
+  f32x16 negl, negd;                                            // -log-sum-exp and -delta of this lane's query
   {
     f32x16 qa[CB], da[CB];
     const T* Gt = static_cast<const T*>(p.Gt) + (long)head * D * p.R2;
@@ -166,8 +173,10 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(BwdArgs p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) dsum += da[cb][e] * frag_elem(of, e);
     }
-    delta = halves_sum(dsum);
-    lse = p.lse[((long)b * p.nH + head) * p.Npad + m];            // +inf for padding tokens
+    const float delta = halves_sum(dsum);
+    const float lse = p.lse[((long)b * p.nH + head) * p.Npad + m];    // +inf for padding tokens
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { negl[e] = -lse; negd[e] = -delta; }
     if (head_ok) {
       if (h == 0) p.delta[((long)b * p.nH + head) * p.Npad + m] = delta;
       T* Qr = static_cast<T*>(p.Qr) + ((tok_base + m) * p.nH + head) * D + 16 * h;
@@ -200,6 +209,7 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(BwdArgs p) {
   const int kv_end = p.causal ? min(p.N, t0 + TQ) : p.N;
   const int n_tiles = (kv_end + BC - 1) / BC;
   const int last = n_tiles - 1;
+  const int lim = p.causal ? min(m, p.N - 1) : p.N - 1;         // last key visible to this lane's query
   s_store(0);
   __syncthreads();
   for (int t = 0; t < n_tiles; ++t) {
@@ -208,34 +218,29 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(BwdArgs p) {
     const T* kbase = st + lr * L::kRow + 16 * h;
     const T* vbase = kbase + L::kKElems;
     const T* tbase = st + 2 * L::kKElems + lr * L::kTRow + 16 * h;
-    f32x16 s[NB], dp[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
+      const int n0 = t * BC + nb * 32;
+      if (p.causal && n0 > tw + 31) continue;                   // every key of the half follows every query
+      // scores start from -log-sum-exp and dP from -delta, so the products form S - lse and dP - delta
+      f32x16 s, dp;
+      mma32_from(s, negl, load_frag<T>(kbase + nb * 32 * L::kRow), qf[0]);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { s[nb][e] = 0.f; dp[nb][e] = 0.f; }
+      for (int cb = 1; cb < CB; ++cb) mma32(s, load_frag<T>(kbase + nb * 32 * L::kRow + cb * 32), qf[cb]);
+      mma32_from(dp, negd, load_frag<T>(vbase + nb * 32 * L::kRow), dof[0]);
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) mma32(s[nb], load_frag<T>(kbase + nb * 32 * L::kRow + cb * 32), qf[cb]);
+      for (int cb = 1; cb < CB; ++cb) mma32(dp, load_frag<T>(vbase + nb * 32 * L::kRow + cb * 32), dof[cb]);
+      if (n0 + 31 >= p.N || (p.causal && n0 + 31 > tw)) {       // a key past the sequence or after a query
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) mma32(dp[nb], load_frag<T>(vbase + nb * 32 * L::kRow + cb * 32), dof[cb]);
-    }
-    const int n0 = t * BC;
-    const int lim = p.causal ? min(m, p.N - 1) : p.N - 1;       // last visible key
-    Frag<T> dsf[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      f32x16 ds;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int n = n0 + nb * 32 + 8 * (e / 4) + 4 * h + (e % 4);
-        const float pr = n > lim ? 0.f : fast_exp2(s[nb][e] - lse);
-        ds[e] = pr * (dp[nb][e] - delta);
+        for (int e = 0; e < 16; ++e)
+          if (n0 + 8 * (e / 4) + 4 * h + (e % 4) > lim) s[e] = -INFINITY;
       }
-      dsf[nb] = to_frag<T>(ds);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = fast_exp2(s[e]) * dp[e];
+      const Frag<T> dsf = to_frag<T>(s);
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) mma32(dq[cb], load_frag<T>(tbase + cb * 32 * L::kTRow + nb * 32), dsf);
     }
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) mma32(dq[cb], load_frag<T>(tbase + cb * 32 * L::kTRow + nb * 32), dsf[nb]);
     s_store((t + 1) & 1);
     __syncthreads();
   }
@@ -267,9 +272,14 @@ template <typename T, int D, int TQ> struct DkvLds {
   static constexpr size_t kBytes = 2ul * kStageBytes;
 };
 
+// Workgroup = 8 waves over 128 keys: waves w and w+4 (one SIMD) own the same 32 keys; wave w
+// accumulates dV^T of them (needs P), wave w+4 accumulates dK^T (needs P and dP).  Both recompute
+// the scores of their keys; splitting the two accumulators over two waves keeps each within the
+// registers of two resident waves per SIMD, so that one wave's exponentials overlap the other's
+// matrix products.
 template <typename T, int D, int TQ>
-__global__ __launch_bounds__(256) void bwd_dkv_kernel(BwdArgs p) {
-  constexpr int CB = D / 32, QBN = TQ / 32, KT = 128, NT = 256;
+__global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
+  constexpr int CB = D / 32, QBN = TQ / 32, KT = 128, NT = 512;
   constexpr int CE = 16 / sizeof(T);
   using L = DkvLds<T, D, TQ>;
   static_assert(L::kStageBytes % 16 == 0, "stages stay 16-byte aligned");
@@ -277,14 +287,15 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(BwdArgs p) {
 
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int h = lane / 32, lr = lane % 32;
+  const bool k_role = wave >= 4;                                // dK^T wave (else dV^T wave)
   const int b = blockIdx.x / p.n_hg, hg = blockIdx.x % p.n_hg;
-  const int key0 = blockIdx.y * KT + 32 * wave;                 // first key of this wave
+  const int key0 = blockIdx.y * KT + 32 * (wave % 4);           // first key of this wave
   const int nk = key0 + lr;                                     // this lane's key
   const bool key_ok = nk < p.Npad;
   const long tok_base = (long)b * p.Npad;
   const long TP = (long)p.Bsz * p.Npad;
 
-  // this wave's keys and values as MFMA column operands, for the whole kernel
+  // this wave's keys (and, for the dK^T wave, values) as MFMA column operands, for the whole kernel
   Frag<T> kf[CB], vf[CB];
   {
     const long row = tok_base + (key_ok ? nk : 0);
@@ -293,14 +304,14 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(BwdArgs p) {
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
       kf[cb] = key_ok ? load_frag<T>(Kg + cb * 32) : zero_frag<T>();
-      vf[cb] = key_ok ? load_frag<T>(Vg + cb * 32) : zero_frag<T>();
+      vf[cb] = key_ok && k_role ? load_frag<T>(Vg + cb * 32) : zero_frag<T>();
     }
   }
-  f32x16 dk[CB], dv[CB];
+  f32x16 acc[CB];                                               // dV^T or dK^T of this wave's keys
 #pragma unroll
   for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) { dk[cb][e] = 0.f; dv[cb][e] = 0.f; }
+    for (int e = 0; e < 16; ++e) acc[cb][e] = 0.f;
 
   // (head, query block) pairs of this workgroup
   const int head0 = hg * p.hpg;
@@ -310,7 +321,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(BwdArgs p) {
   const int n_it = n_heads * n_qb;
 
   constexpr int RCH = TQ * D / CE, PT = (RCH + NT - 1) / NT;    // chunks per tensor, per thread
-  static_assert(RCH % NT == 0, "tile must fill all threads");
+  constexpr bool FULL = RCH % NT == 0;
   constexpr int RCPR = D / CE, TCPR = TQ / CE;
   u32x4 qreg[PT], oreg[PT], qtreg[PT], otreg[PT];
   float statreg = 0.f;
@@ -324,6 +335,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(BwdArgs p) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int ci = threadIdx.x + i * NT;
+      if (!FULL && ci >= RCH) break;
       const int row = ci / RCPR, cc = ci % RCPR;
       qreg[i] = *reinterpret_cast<const u32x4*>(Qg + (long)row * p.nH * D + cc * CE);
       oreg[i] = *reinterpret_cast<const u32x4*>(Og + (long)row * p.nH * D + cc * CE);
@@ -346,6 +358,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(BwdArgs p) {
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int ci = threadIdx.x + i * NT;
+      if (!FULL && ci >= RCH) break;
       const int row = ci / RCPR, cc = ci % RCPR;
       *reinterpret_cast<u32x4*>(qs + row * L::kRow + cc * CE) = qreg[i];
       *reinterpret_cast<u32x4*>(os + row * L::kRow + cc * CE) = oreg[i];
@@ -353,8 +366,9 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(BwdArgs p) {
       *reinterpret_cast<u32x4*>(qts + trow * L::kTRow + tc * CE) = qtreg[i];
       *reinterpret_cast<u32x4*>(ots + trow * L::kTRow + tc * CE) = otreg[i];
     }
-    if (threadIdx.x < TQ) stat[threadIdx.x] = statreg;
-    else if (threadIdx.x >= 128 && threadIdx.x < 128 + TQ) stat[TQ + threadIdx.x - 128] = statreg;
+    // stored negated: a score block starts from -log-sum-exp, a dP block from -delta
+    if (threadIdx.x < TQ) stat[threadIdx.x] = -statreg;
+    else if (threadIdx.x >= 128 && threadIdx.x < 128 + TQ) stat[TQ + threadIdx.x - 128] = -statreg;
   };
 
   g_load(0);
@@ -374,51 +388,60 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(BwdArgs p) {
       const int qfirst = q0 + 32 * qb;
       // all 32 keys of the wave lie after all 32 queries of the block: nothing to do
       if (p.causal && key0 > qfirst + 31) continue;
-      f32x16 s, dp;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
-      const T* qrow = qs + (qb * 32 + lr) * L::kRow + 16 * h;
-      const T* orow = os + (qb * 32 + lr) * L::kRow + 16 * h;
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb) mma32(s, load_frag<T>(qrow + cb * 32), kf[cb]);
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb) mma32(dp, load_frag<T>(orow + cb * 32), vf[cb]);
-      f32x16 pr, ds;
+      f32x16 s;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + qb * 32 + 8 * q + 4 * h);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + TQ + qb * 32 + 8 * q + 4 * h);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int mq = qfirst + 8 * q + 4 * h + e;            // query of this register
-          const bool masked = nk >= p.N || (p.causal && nk > mq);
-          const float v = masked ? 0.f : fast_exp2(s[4 * q + e] - l4[e]);
-          pr[4 * q + e] = v;
-          ds[4 * q + e] = v * (dp[4 * q + e] - d4[e]);
+        for (int e = 0; e < 4; ++e) s[4 * q + e] = l4[e];
+      }
+      const T* qrow = qs + (qb * 32 + lr) * L::kRow + 16 * h;
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) mma32(s, load_frag<T>(qrow + cb * 32), kf[cb]);
+      if (key0 + 31 >= p.N || (p.causal && key0 + 31 > qfirst)) {   // a key past the sequence or after a query
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int mq = qfirst + 8 * (e / 4) + 4 * h + (e % 4);    // query of this register
+          if (nk >= p.N || (p.causal && nk > mq)) s[e] = -INFINITY;
         }
       }
-      const Frag<T> pf = to_frag<T>(pr), dsf = to_frag<T>(ds);
-      const T* otrow = ots + lr * L::kTRow + qb * 32 + 16 * h;
-      const T* qtrow = qts + lr * L::kTRow + qb * 32 + 16 * h;
+      if (!k_role) {
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) mma32(dv[cb], load_frag<T>(otrow + cb * 32 * L::kTRow), pf);
+        for (int e = 0; e < 16; ++e) s[e] = fast_exp2(s[e]);
+        const Frag<T> pf = to_frag<T>(s);
+        const T* otrow = ots + lr * L::kTRow + qb * 32 + 16 * h;
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) mma32(dk[cb], load_frag<T>(qtrow + cb * 32 * L::kTRow), dsf);
+        for (int cb = 0; cb < CB; ++cb) mma32(acc[cb], load_frag<T>(otrow + cb * 32 * L::kTRow), pf);
+      } else {
+        f32x16 dp;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + TQ + qb * 32 + 8 * q + 4 * h);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dp[4 * q + e] = d4[e];
+        }
+        const T* orow = os + (qb * 32 + lr) * L::kRow + 16 * h;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) mma32(dp, load_frag<T>(orow + cb * 32), vf[cb]);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[e] = fast_exp2(s[e]) * dp[e];
+        const Frag<T> dsf = to_frag<T>(s);
+        const T* qtrow = qts + lr * L::kTRow + qb * 32 + 16 * h;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) mma32(acc[cb], load_frag<T>(qtrow + cb * 32 * L::kTRow), dsf);
+      }
     }
     s_store((it + 1) & 1);
     __syncthreads();
   }
 
   if (key_ok) {
-    float* dK = p.dKp + ((long)hg * TP + tok_base + nk) * D + 4 * h;
-    float* dV = p.dVp + ((long)hg * TP + tok_base + nk) * D + 4 * h;
+    float* dst = (k_role ? p.dKp : p.dVp) + ((long)hg * TP + tok_base + nk) * D + 4 * h;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        store4(dK + cb * 32 + 8 * q, dk[cb][4 * q], dk[cb][4 * q + 1], dk[cb][4 * q + 2], dk[cb][4 * q + 3]);
-        store4(dV + cb * 32 + 8 * q, dv[cb][4 * q], dv[cb][4 * q + 1], dv[cb][4 * q + 2], dv[cb][4 * q + 3]);
-      }
+      for (int q = 0; q < 4; ++q)
+        store4(dst + cb * 32 + 8 * q, acc[cb][4 * q], acc[cb][4 * q + 1], acc[cb][4 * q + 2], acc[cb][4 * q + 3]);
   }
 }
 
@@ -465,12 +488,12 @@ __global__ __launch_bounds__(256) void kv_reduce_kernel(KvReduceArgs a) {
 // ---- launchers ---------------------------------------------------------------------------------------
 template <typename T, int D, int BC>
 static hipError_t dq_one(const BwdArgs& a, hipStream_t s) {
-  dim3 grid(((a.nH + 3) / 4) * a.Bsz, a.Npad / 32);
+  dim3 grid(((a.nH + 3) / 4) * a.Bsz, a.Npad / 64);
   const size_t smem = DqLds<T, D, BC>::kBytes;
   auto kern = bwd_dq_kernel<T, D, BC>;
   static LdsOnce lds_once;
   if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
-  hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, a);
+  hipLaunchKernelGGL(kern, grid, dim3(512), smem, s, a);
   return hipGetLastError();
 }
 
@@ -498,7 +521,7 @@ static hipError_t dkv_one(const BwdArgs& a, hipStream_t s) {
   auto kern = bwd_dkv_kernel<T, D, TQ>;
   static LdsOnce lds_once;
   if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
-  hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, a);
+  hipLaunchKernelGGL(kern, grid, dim3(512), smem, s, a);
   return hipGetLastError();
 }
 
