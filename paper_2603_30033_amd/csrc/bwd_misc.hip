@@ -10,38 +10,53 @@ namespace ta {
 // natural index of the element stored at position p of an acc-ordered 32-block
 __device__ __forceinline__ int acc_index(int p) { return 8 * ((p >> 2) & 3) + 4 * (p >> 4) + (p & 3); }
 
+// Each thread moves one CE x CE block (CE = elements per 16 bytes) and transposes it in registers:
+// CE loads of 16 bytes from CE consecutive token rows, CE stores of 16 bytes to CE consecutive
+// output rows.  Lanes are arranged 8 (column chunks) x 8 (token blocks), so every load and every
+// store instruction of a wave touches whole 128-byte lines; no LDS.
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_kernel(TransposeArgs a) {
-  __shared__ float tile[32][33];
+  constexpr int CE = 16 / sizeof(T);
+  typedef T Vec __attribute__((ext_vector_type(CE)));
   const long TP = (long)a.Bsz * a.Npad;
-  const int t0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
-  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int lc = lane % 8, lt = lane / 8;
+  const int t0 = (blockIdx.x * 4 + wave) * 8 * CE + lt * CE;     // first token of this thread's block
+  const int c0 = blockIdx.y * 8 * CE + lc * CE;                  // first source column
+  if (t0 >= TP || c0 >= a.cols_pad) return;
   const T* src = static_cast<const T*>(a.src);
+  Vec in[CE];
 #pragma unroll
-  for (int rr = 0; rr < 4; ++rr) {
-    const int tp = t0 + ty + 8 * rr;                            // < TP: TP is a multiple of 64
+  for (int i = 0; i < CE; ++i) {
+    const int tp = t0 + i;
     long row = tp;
-    bool ok = c0 + tx < a.cols;
+    bool ok = c0 < a.cols;                                       // cols is a multiple of CE
     if (!a.src_padded) {
       const int b = tp / a.Npad, n = tp % a.Npad;
       ok = ok && n < a.N;
       row = (long)b * a.N + n;
     }
-    tile[ty + 8 * rr][tx] = ok ? to_f32(src[row * a.ld + c0 + tx]) : 0.f;
+    Vec z;
+#pragma unroll
+    for (int k = 0; k < CE; ++k) z[k] = (T)0.f;
+    in[i] = ok ? *reinterpret_cast<const Vec*>(src + row * a.ld + c0) : z;
   }
-  __syncthreads();
   T* dst = static_cast<T*>(a.dst);
 #pragma unroll
-  for (int rr = 0; rr < 4; ++rr) {
-    const int p = ty + 8 * rr;                                  // stored column position inside the block
-    const int c = c0 + (a.unperm ? acc_index(p) : p);
-    store1(dst + (long)c * TP + t0 + tx, tile[tx][p]);
+  for (int k = 0; k < CE; ++k) {
+    Vec out;
+#pragma unroll
+    for (int i = 0; i < CE; ++i) out[i] = in[i][k];
+    const int col = c0 + k;
+    const int c = a.unperm ? (col & ~31) + acc_index(col & 31) : col;
+    *reinterpret_cast<Vec*>(dst + (long)c * TP + t0) = out;
   }
 }
 
 hipError_t launch_transpose(int dtype, const TransposeArgs& a, hipStream_t s) {
   const long TP = (long)a.Bsz * a.Npad;
-  dim3 grid((unsigned)(TP / 32), (unsigned)(a.cols_pad / 32));
+  const int ce = dtype == 0 ? 4 : 8;
+  dim3 grid((unsigned)((TP + 32 * ce - 1) / (32 * ce)), (unsigned)((a.cols_pad + 8 * ce - 1) / (8 * ce)));
   if (dtype == 0)
     hipLaunchKernelGGL(transpose_kernel<float>, grid, dim3(256), 0, s, a);
   else
@@ -60,8 +75,19 @@ __global__ __launch_bounds__(256) void core_grad_kernel(CoreGradArgs g) {
   if ((int)blockIdx.x < nC) {
     const int a = blockIdx.x / g.r2, b = blockIdx.x % g.r2;
     for (int c = threadIdx.x; c < g.r3; c += 256) {
+      // eight heads per round: their loads are all in flight before the first is used
       float acc = 0.f;
-      for (int i = 0; i < g.nH; ++i) acc += to_f32(U1[(long)i * g.r1 + a]) * g.dG[(long)b * ldg + (long)i * g.D + c];
+      for (int i0 = 0; i0 < g.nH; i0 += 8) {
+        float u[8], v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int i = min(i0 + k, g.nH - 1);
+          u[k] = to_f32(U1[(long)i * g.r1 + a]);
+          v[k] = g.dG[(long)b * ldg + (long)i * g.D + c];
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc += i0 + k < g.nH ? u[k] * v[k] : 0.f;
+      }
       g.dC[((long)a * g.r2 + b) * g.r3 + c] = g.scale * acc;
     }
     return;
@@ -69,9 +95,18 @@ __global__ __launch_bounds__(256) void core_grad_kernel(CoreGradArgs g) {
   const int e = blockIdx.x - nC;
   const int i = e / g.r1, a = e % g.r1;
   float acc = 0.f;
-  for (int j = threadIdx.x; j < g.r2 * g.r3; j += 256) {
-    const int b = j / g.r3, c = j % g.r3;
-    acc += g.dG[(long)b * ldg + (long)i * g.D + c] * to_f32(C[((long)a * g.r2 + b) * g.r3 + c]);
+  const int n = g.r2 * g.r3;
+  for (int j0 = threadIdx.x; j0 < n; j0 += 8 * 256) {
+    float u[8], v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int j = min(j0 + k * 256, n - 1);
+      const int b = j / g.r3, c = j % g.r3;
+      u[k] = g.dG[(long)b * ldg + (long)i * g.D + c];
+      v[k] = to_f32(C[((long)a * g.r2 + b) * g.r3 + c]);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc += j0 + k * 256 < n ? u[k] * v[k] : 0.f;
   }
   __shared__ float red[256];
   red[threadIdx.x] = acc;
