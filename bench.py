@@ -134,8 +134,11 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="llama7b_n4096")
-    ap.add_argument("--pass", dest="which", choices=["forward", "backward"], default="forward",
-                    help="backward: one step = one tucker_attn_backward call (prefill workloads only)")
+    ap.add_argument("--pass", dest="which", choices=["forward", "backward", "backward_self_contained"],
+                    default="forward",
+                    help="backward: one step = one tucker_attn_backward call on the state a forward call left in "
+                         "the shared workspace (the forward is run once, untimed); backward_self_contained: the "
+                         "backward call re-runs the forward inside (prefill workloads only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also launch a plain device-to-device copy of this many MiB (three times), so that a "
@@ -160,7 +163,8 @@ def main():
     inp = wl.make_inputs(w)
     K, W = args.steps, args.warmup
     fl = flops(w)
-    backward = args.which == "backward"
+    backward = args.which != "forward"
+    saved = args.which == "backward"
     if backward and w.mode == "decode":
         log("a decode step has no backward pass")
         sys.exit(2)
@@ -175,7 +179,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    with Layer(w, inp) as layer:
+    with Layer(w, inp, save_for_backward=backward and saved) as layer:
         if w.mode == "decode":
             x = to_device(inp["X"][:, 0], w.dtype)
             y = torch.empty_like(x)
@@ -205,9 +209,13 @@ def main():
                 grads = {"d" + k: torch.empty(v.shape, dtype=torch.float32, device="cuda")
                          for k, v in layer.weights.items()}
                 ws = layer.workspace(ta.tucker_attn_backward_workspace_bytes(layer.ctx, w.B, w.N))
+                dX = torch.empty_like(X)
+                if saved:
+                    ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, w.pos0, None, None, ws)
 
                 def step():
-                    ta.tucker_attn_backward(layer.ctx, layer.weights, X, dY, Y, grads, w.pos0, ws)
+                    ta.tucker_attn_backward(layer.ctx, layer.weights, X, dY, dX, grads, w.pos0, ws,
+                                            forward_state=saved)
             else:
                 def step():
                     ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, w.pos0, None, None, ws)

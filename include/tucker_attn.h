@@ -73,6 +73,11 @@ typedef struct {
                           /* latent; needs rt3 == r3; weights.Ut3 is ignored (may be NULL); ONE    */
                           /* cache [B, Lmax, r3] holds the UNROTATED latent and keys are rotated   */
                           /* when a cache tile is read                                             */
+  int32_t save_for_backward; /* 0 | 1: training.  tucker_attn_forward then also leaves what the    */
+                          /* backward pass needs (log-sum-exp of every query and head, value rows, */
+                          /* transposed keys) in its workspace, and tucker_attn_workspace_bytes     */
+                          /* returns the size of the backward workspace, so that one buffer serves  */
+                          /* a forward call and the backward call that follows it                   */
 } tucker_attn_config;
 
 /* Device pointers to the weights; read-only, caller-owned. */
@@ -100,7 +105,7 @@ int tucker_attn_create(const tucker_attn_config *cfg, tucker_attn_ctx **out);
 void tucker_attn_destroy(tucker_attn_ctx *ctx);
 
 /* Bytes of device workspace tucker_attn_forward needs for a batch of B sequences of N
- * tokens; 0 if an argument is invalid. */
+ * tokens (with save_for_backward: what tucker_attn_backward needs); 0 if an argument is invalid. */
 size_t tucker_attn_workspace_bytes(const tucker_attn_ctx *ctx, int32_t B, int32_t N);
 
 /* Bytes of device workspace tucker_attn_decode needs for B sequences; 0 if invalid. */
@@ -167,13 +172,17 @@ size_t tucker_attn_backward_workspace_bytes(const tucker_attn_ctx *ctx, int32_t 
  *   dY   device [B, N, d]   in: upstream gradient, storage type
  *   dX   device [B, N, d]   out: gradient of X, storage type
  *   grads                   out: gradients of the eight weight arrays (seven with shared_kv), fp32
- * The call is self-contained: it re-runs the forward up to the head merge inside its own
- * workspace (no state of an earlier tucker_attn_forward call is used), then the backward kernels.
+ *   forward_state  0: the call is self-contained; it re-runs the forward up to the head merge inside
+ *                  its own workspace, then the backward kernels.
+ *                  1: the workspace is the one a tucker_attn_forward call of this context (created
+ *                  with save_for_backward = 1) just used with the same w, X, B, N and pos0, and nothing
+ *                  has written to it since: the forward is not run again.  INVALID_ARG if the context
+ *                  was created without save_for_backward.
  * Same shape limits as forward, and B * roundup(N, 64) <= 2^21 tokens.
  */
 int tucker_attn_backward(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
                          const void *X, const void *dY, void *dX, const tucker_attn_grads *grads,
-                         int32_t B, int32_t N, int32_t pos0,
+                         int32_t B, int32_t N, int32_t pos0, int32_t forward_state,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*

@@ -33,7 +33,8 @@ class tucker_attn_config(C.Structure):
                 ("r1", C.c_int32), ("r2", C.c_int32), ("r3", C.c_int32),
                 ("rt1", C.c_int32), ("rt2", C.c_int32), ("rt3", C.c_int32),
                 ("causal", C.c_int32), ("use_rope", C.c_int32), ("rope_base", C.c_float),
-                ("dtype", C.c_int32), ("max_positions", C.c_int32), ("shared_kv", C.c_int32)]
+                ("dtype", C.c_int32), ("max_positions", C.c_int32), ("shared_kv", C.c_int32),
+                ("save_for_backward", C.c_int32)]
 
 
 class tucker_attn_weights(C.Structure):
@@ -80,7 +81,7 @@ def load_library() -> C.CDLL:
     lib.tucker_attn_backward_workspace_bytes.argtypes = [ctx_p, C.c_int32, C.c_int32]
     lib.tucker_attn_backward_workspace_bytes.restype = C.c_size_t
     lib.tucker_attn_backward.argtypes = [ctx_p, C.POINTER(tucker_attn_weights), C.c_void_p, C.c_void_p, C.c_void_p,
-                                         C.POINTER(tucker_attn_grads), C.c_int32, C.c_int32, C.c_int32,
+                                         C.POINTER(tucker_attn_grads), C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_void_p, C.c_size_t, C.c_void_p]
     lib.tucker_attn_backward.restype = C.c_int
     lib.tucker_attn_profile_enable.argtypes = [ctx_p, C.c_int32]
@@ -113,12 +114,13 @@ def _stream_ptr(stream) -> Optional[int]:
 
 
 def tucker_attn_create(*, d_model, n_heads, d_head, r1, r2, r3, rt1=None, rt2=None, rt3=None, causal=True,
-                       rope_base=None, dtype="bf16", max_positions=1, shared_kv=False) -> int:
+                       rope_base=None, dtype="bf16", max_positions=1, shared_kv=False,
+                       save_for_backward=False) -> int:
     """Returns an opaque context handle (int).  Needs a current HIP device when rope_base is set."""
     cfg = tucker_attn_config(d_model, n_heads, d_head, r1, r2, r3, rt1 or r1, rt2 or r2, rt3 or r3,
                              int(bool(causal)), int(rope_base is not None), float(rope_base or 0.0),
                              {"f32": TUCKER_ATTN_F32, "bf16": TUCKER_ATTN_BF16}[dtype], int(max_positions),
-                             int(bool(shared_kv)))
+                             int(bool(shared_kv)), int(bool(save_for_backward)))
     ctx = C.c_void_p()
     _check(load_library().tucker_attn_create(C.byref(cfg), C.byref(ctx)), "tucker_attn_create")
     return ctx.value
@@ -179,15 +181,16 @@ def tucker_attn_backward_workspace_bytes(ctx: int, B: int, N: int) -> int:
 
 
 def tucker_attn_backward(ctx: int, weights: Dict, X, dY, dX, grads: Dict, pos0: int = 0, workspace=None,
-                         stream=None, check: bool = True) -> int:
+                         stream=None, check: bool = True, forward_state: bool = False) -> int:
     """X, dY, dX: contiguous device tensors [B, N, d] of the storage type; grads: dict of contiguous fp32
     device tensors keyed dC, dU1, dU2, dU3, dCt, dUt1, dUt2 and (unless the latent is shared) dUt3,
-    shaped like the weights; all are overwritten."""
+    shaped like the weights; all are overwritten.  forward_state: the workspace is the one the
+    forward call of a save_for_backward context just used with the same inputs."""
     B, N = int(X.shape[0]), int(X.shape[1])
     ws = _weights_struct(weights)
     gs = tucker_attn_grads(*[_ptr(grads.get(k)) for k in GRAD_KEYS])
     st = load_library().tucker_attn_backward(ctx, C.byref(ws), X.data_ptr(), dY.data_ptr(), dX.data_ptr(),
-                                             C.byref(gs), B, N, int(pos0),
+                                             C.byref(gs), B, N, int(pos0), int(bool(forward_state)),
                                              _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                              _stream_ptr(stream))
     if check:

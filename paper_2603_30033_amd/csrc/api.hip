@@ -320,6 +320,7 @@ int tucker_attn_create(const tucker_attn_config* cfg, tucker_attn_ctx** out) {
   if (f.dtype != TUCKER_ATTN_F32 && f.dtype != TUCKER_ATTN_BF16) return TUCKER_ATTN_INVALID_ARG;
   if ((f.causal != 0 && f.causal != 1) || (f.use_rope != 0 && f.use_rope != 1)) return TUCKER_ATTN_INVALID_ARG;
   if (f.shared_kv != 0 && f.shared_kv != 1) return TUCKER_ATTN_INVALID_ARG;
+  if (f.save_for_backward != 0 && f.save_for_backward != 1) return TUCKER_ATTN_INVALID_ARG;
   if (f.shared_kv && f.rt3 != f.r3) return TUCKER_ATTN_INVALID_ARG;
   if (f.use_rope && !(f.rope_base > 0.f)) return TUCKER_ATTN_INVALID_ARG;
   if (f.r3 > 128 || f.rt3 > 128 || f.r2 > 512 || f.rt2 > 512 || f.r1 > 64 || f.rt1 > 64)
@@ -381,6 +382,7 @@ void tucker_attn_destroy(tucker_attn_ctx* c) {
 
 size_t tucker_attn_workspace_bytes(const tucker_attn_ctx* c, int32_t B, int32_t N) {
   if (!c || B < 1 || N < 1) return 0;
+  if (c->cfg.save_for_backward) return carve_backward(c, nullptr, B, N).bytes;
   return carve_prefill(c, nullptr, B, N).bytes;
 }
 
@@ -402,7 +404,15 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
   if ((long)B * pad64(N) > (1l << 30) / 64 || B > 65535) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
   PrefillWs ws = carve_prefill(c, workspace, B, N);
-  if (workspace_bytes < ws.bytes) return TUCKER_ATTN_WORKSPACE_TOO_SMALL;
+  void *Vr = nullptr, *Krt = nullptr;
+  float* lse = nullptr;
+  size_t need = ws.bytes;
+  if (f.save_for_backward) {                                    // the backward layout, of which ws is the head
+    if ((long)B * pad64(N) > (1l << 21)) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+    const BackwardWs bw = carve_backward(c, workspace, B, N);
+    Vr = bw.Vr; Krt = bw.Krt; lse = bw.lse; need = bw.bytes;
+  }
+  if (workspace_bytes < need) return TUCKER_ATTN_WORKSPACE_TOO_SMALL;
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int Npad = pad64(N);
@@ -411,7 +421,7 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
   if (rec.begin() != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
   const void* ut2;
   long ut2_ld;
-  if (int st = forward_core(c, w, X, B, N, pos0, Kcache_out, Vcache_out, Lmax, ws, nullptr, nullptr, nullptr, s, rec,
+  if (int st = forward_core(c, w, X, B, N, pos0, Kcache_out, Vcache_out, Lmax, ws, Vr, Krt, lse, s, rec,
                             &ut2, &ut2_ld);
       st != TUCKER_ATTN_OK)
     return st;
@@ -435,13 +445,15 @@ size_t tucker_attn_backward_workspace_bytes(const tucker_attn_ctx* c, int32_t B,
 }
 
 int tucker_attn_backward(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* X, const void* dY, void* dX,
-                         const tucker_attn_grads* gr, int32_t B, int32_t N, int32_t pos0, void* workspace,
-                         size_t workspace_bytes, void* hip_stream) {
+                         const tucker_attn_grads* gr, int32_t B, int32_t N, int32_t pos0, int32_t forward_state,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!c || !weights_ok(c, w) || !X || !dY || !dX || !gr || !workspace) return TUCKER_ATTN_INVALID_ARG;
   const tucker_attn_config& f = c->cfg;
   if (!gr->dC || !gr->dU1 || !gr->dU2 || !gr->dU3 || !gr->dCt || !gr->dUt1 || !gr->dUt2) return TUCKER_ATTN_INVALID_ARG;
   if (f.shared_kv ? gr->dUt3 != nullptr : gr->dUt3 == nullptr) return TUCKER_ATTN_INVALID_ARG;
   if (B < 1 || N < 1 || pos0 < 0) return TUCKER_ATTN_INVALID_ARG;
+  if (forward_state != 0 && forward_state != 1) return TUCKER_ATTN_INVALID_ARG;
+  if (forward_state && !f.save_for_backward) return TUCKER_ATTN_INVALID_ARG;
   if (f.use_rope && (long)pos0 + N > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
   if ((long)B * pad64(N) > (1l << 21) || B > 65535) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
@@ -456,11 +468,13 @@ int tucker_attn_backward(tucker_attn_ctx* c, const tucker_attn_weights* w, const
   if (rec.begin() != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
 
   // ---- forward intermediates: Qlat, K, V (three layouts), O, log-sum-exp, Z ----------------------------
-  const void* ut2;
-  long ut2_ld;
-  if (int st = forward_core(c, w, X, B, N, pos0, nullptr, nullptr, 0, ws.f, ws.Vr, ws.Krt, ws.lse, s, rec, &ut2, &ut2_ld);
-      st != TUCKER_ATTN_OK)
-    return st;
+  if (!forward_state) {
+    const void* ut2;
+    long ut2_ld;
+    if (int st = forward_core(c, w, X, B, N, pos0, nullptr, nullptr, 0, ws.f, ws.Vr, ws.Krt, ws.lse, s, rec, &ut2, &ut2_ld);
+        st != TUCKER_ATTN_OK)
+      return st;
+  }
 
   // ---- weights in the layouts of the backward products ------------------------------------------------------
   {

@@ -30,7 +30,8 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 class Layer:
     """A context plus device copies of one workload's weights."""
 
-    def __init__(self, w: wl.Workload, inp: Dict[str, np.ndarray], max_positions: Optional[int] = None):
+    def __init__(self, w: wl.Workload, inp: Dict[str, np.ndarray], max_positions: Optional[int] = None,
+                 save_for_backward: bool = False):
         self.w = w
         rt1, rt2, rt3 = w.ranks_post()
         if max_positions is None:
@@ -38,7 +39,7 @@ class Layer:
         self.ctx = ta.tucker_attn_create(
             d_model=w.d_model, n_heads=w.n_heads, d_head=w.d_head, r1=w.r1, r2=w.r2, r3=w.r3,
             rt1=rt1, rt2=rt2, rt3=rt3, causal=w.causal, rope_base=w.rope_base, dtype=w.dtype,
-            max_positions=max_positions, shared_kv=w.shared_kv)
+            max_positions=max_positions, shared_kv=w.shared_kv, save_for_backward=save_for_backward)
         # with a shared key-value projection the library never reads the value basis: it gets none
         self.weights = {k: to_device(inp[k], w.dtype) for k in W_KEYS if not (w.shared_kv and k == "Ut3")}
         self._ws = None
@@ -67,13 +68,14 @@ class Layer:
         ta.tucker_attn_forward(self.ctx, self.weights, X, Y, pos0, Kc, Vc, ws)
         return Y
 
-    def backward(self, X: torch.Tensor, dY: torch.Tensor, pos0: int = 0):
-        """Returns (dX, dict of fp32 weight gradients)."""
+    def backward(self, X: torch.Tensor, dY: torch.Tensor, pos0: int = 0, forward_state: bool = False):
+        """Returns (dX, dict of fp32 weight gradients).  forward_state: reuse what the forward call just
+        before left in the shared workspace (needs a layer made with save_for_backward)."""
         B, N = X.shape[0], X.shape[1]
         dX = torch.empty_like(X)
         grads = {"d" + k: torch.empty(self.weights[k].shape, dtype=torch.float32, device="cuda") for k in self.weights}
         ws = self.workspace(ta.tucker_attn_backward_workspace_bytes(self.ctx, B, N))
-        ta.tucker_attn_backward(self.ctx, self.weights, X, dY, dX, grads, pos0, ws)
+        ta.tucker_attn_backward(self.ctx, self.weights, X, dY, dX, grads, pos0, ws, forward_state=forward_state)
         return dX, grads
 
     def decode(self, x: torch.Tensor, Kc: torch.Tensor, Vc: Optional[torch.Tensor], kv_len, y=None) -> torch.Tensor:

@@ -104,3 +104,50 @@ def test_backward_llama_shape_scaled():
 def test_backward_paper_rank_shapes_scaled():
     run_case(wl.scaled(wl.WORKLOADS["gpt2_r8_128_64"], B=2, N=300))
     run_case(wl.scaled(wl.WORKLOADS["llama1b_r32_128_128"], B=1, N=320))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_from_saved_forward_state(dtype):
+    # a training step: forward with save_for_backward, then backward without re-running the forward;
+    # both results against their oracles, and the gradients equal to the self-contained call's bit for bit
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=203, d_model=128, n_heads=5, d_head=32, r1=3, r2=48, r3=40,
+                  rt1=2, rt2=72, rt3=56, dtype=dtype, pos0=3, seed=41)
+    inp = wl.make_inputs(w)
+    dY = upstream(w, 101)
+    with Layer(w, inp, max_positions=w.pos0 + w.N, save_for_backward=True) as layer:
+        X, dYd = to_device(inp["X"], w.dtype), to_device(dY, w.dtype)
+        Y = layer.forward(X, pos0=w.pos0)
+        dX, grads = layer.backward(X, dYd, pos0=w.pos0, forward_state=True)
+        torch.cuda.synchronize()
+        got = {k: to_host(v) for k, v in grads.items()}
+        got["dX"] = to_host(dX)
+        y = to_host(Y)
+        dX2, grads2 = layer.backward(X, dYd, pos0=w.pos0, forward_state=False)
+        torch.cuda.synchronize()
+        assert torch.equal(dX, dX2)
+        for k in ("dU2", "dUt2", "dC", "dCt"):
+            assert torch.equal(grads[k], grads2[k]), k
+    ref_y = orc.per_head_forward(inp["X"], wl.weights_of(inp), w.d_head, w.causal, w.rope_base, pos0=w.pos0)
+    assert orc.relative_l2(y, ref_y) <= TOL[dtype]
+    check_all(got, oracle_backward(w, inp, dY), dtype, "saved forward state")
+
+
+def test_backward_argument_errors():
+    from paper_2603_30033_amd import binding as ta
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], N=40)
+    inp = wl.make_inputs(w)
+    with Layer(w, inp) as layer:
+        X = to_device(inp["X"], w.dtype)
+        dX = torch.empty_like(X)
+        grads = {"d" + k: torch.empty(v.shape, dtype=torch.float32, device="cuda") for k, v in layer.weights.items()}
+        ws = layer.workspace(ta.tucker_attn_backward_workspace_bytes(layer.ctx, w.B, w.N))
+        ok = ta.tucker_attn_backward(layer.ctx, layer.weights, X, X, dX, grads, 0, ws, check=False)
+        assert ok == 0
+        # saved state asked of a context that does not save it
+        assert ta.tucker_attn_backward(layer.ctx, layer.weights, X, X, dX, grads, 0, ws, check=False,
+                                       forward_state=True) == -1
+        # a missing gradient buffer, a workspace that is too small
+        g2 = dict(grads); g2.pop("dU3")
+        assert ta.tucker_attn_backward(layer.ctx, layer.weights, X, X, dX, g2, 0, ws, check=False) == -1
+        assert ta.tucker_attn_backward(layer.ctx, layer.weights, X, X, dX, grads, 0, ws[:1024], check=False) == -3
+        torch.cuda.synchronize()
