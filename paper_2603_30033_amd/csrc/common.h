@@ -160,6 +160,18 @@ template <> __device__ __forceinline__ Frag<bf16> load_frag_major<bf16>(const bf
   return f;
 }
 
+template <typename T> __device__ __forceinline__ void store_frag_major(T* block, int lane, const Frag<T>& f);
+template <> __device__ __forceinline__ void store_frag_major<float>(float* block, int lane, const Frag<float>& f) {
+  f32x4* q = reinterpret_cast<f32x4*>(block) + lane;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) q[64 * i] = f.v[i];
+}
+template <> __device__ __forceinline__ void store_frag_major<bf16>(bf16* block, int lane, const Frag<bf16>& f) {
+  bf16x8* q = reinterpret_cast<bf16x8*>(block) + lane;
+  q[0] = f.v[0];
+  q[64] = f.v[1];
+}
+
 // four consecutive accumulator registers (rows 8q+4h .. +3) -> 4 elements of T at p (natural order)
 __device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
   *reinterpret_cast<f32x4*>(p) = f32x4{a, b, c, d};
