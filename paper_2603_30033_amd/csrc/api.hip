@@ -81,7 +81,7 @@ PrefillWs carve_prefill(const tucker_attn_ctx* c, void* ws, int B, int N) {
 struct BackwardWs {
   PrefillWs f;
   float *lse, *delta, *dKp, *dVp, *dG, *dGt, *part;
-  void *Vr, *Krt, *Ut2T, *Gtil_t, *G2, *Wb, *dZ, *Qr, *dO, *dQ, *Qt, *dOt, *dQt, *dLat;
+  void *Vr, *Krt, *Ut2T, *Gtil_t, *G2, *Wb, *dZ, *Qr, *dO, *dQ, *dQt, *dLat;
   void *Xt, *dYt, *dLat_t, *Zt, *Qlat_t, *dZt, *Ot;
   int LW;            // width of the latent-gradient rows: R2 + D (shared latent) or R2 + 2 D
   int hpg, n_hg;     // heads per group / number of groups of the key-value gradient kernel
@@ -124,8 +124,6 @@ BackwardWs carve_backward(const tucker_attn_ctx* c, void* ws, int B, int N) {
   w.Qr = cv.take<char>(TP * nHD * es);
   w.dO = cv.take<char>(TP * nHD * es);
   w.dQ = cv.take<char>(TP * nHD * es);
-  w.Qt = cv.take<char>(TP * nHD * es);
-  w.dOt = cv.take<char>(TP * nHD * es);
   w.dQt = cv.take<char>(TP * nHD * es);
   w.dKp = cv.take<float>((size_t)w.n_hg * TP * c->D * 4);
   w.dVp = cv.take<float>((size_t)w.n_hg * TP * c->D * 4);
@@ -514,7 +512,7 @@ int tucker_attn_backward(tucker_attn_ctx* c, const tucker_attn_weights* w, const
   BwdArgs a;
   std::memset(&a, 0, sizeof(a));
   a.Qlat = ws.f.Qlat; a.Gt = ws.f.Gt; a.dZ = ws.dZ; a.Gtil_t = ws.Gtil_t; a.Kr = ws.f.Kr; a.Vr = ws.Vr; a.Krt = ws.Krt;
-  a.O = ws.f.O; a.lse = ws.lse; a.delta = ws.delta; a.Qr = ws.Qr; a.dO = ws.dO; a.Qt = ws.Qt; a.dOt = ws.dOt;
+  a.O = ws.f.O; a.lse = ws.lse; a.delta = ws.delta; a.Qr = ws.Qr; a.dO = ws.dO;
   a.dQ = ws.dQ; a.dQt = ws.dQt; a.dKp = ws.dKp; a.dVp = ws.dVp; a.rope = c->rope; a.rope_ld = f.max_positions;
   a.Bsz = B; a.N = N; a.Npad = Npad; a.nH = f.n_heads; a.R2 = c->R2; a.RT2 = c->RT2; a.D = c->D;
   a.causal = f.causal; a.pos0 = pos0; a.hpg = ws.hpg; a.n_hg = ws.n_hg;

@@ -11,7 +11,7 @@
 // Two kernels, neither with atomics:
 //   bwd_dq   one wave = 32 queries of one head, walks the key tiles like the forward kernel:
 //            builds Q_i and dO_i in a prologue from the latent query and dZ (and leaves copies of
-//            both, plain and transposed, for the second kernel), accumulates dQ_i, removes the
+//            both for the second kernel), accumulates dQ_i, removes the
 //            rotation and stores it (plain for the latent-query gradient, transposed for the
 //            gradient of the core).
 //   bwd_dkv  a pair of waves = 32 keys kept in registers as operands, walks (head, query block)
@@ -183,21 +183,10 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs p) {
       if (h == 0) p.delta[((long)b * p.nH + head) * p.Npad + m] = delta;
       T* Qr = static_cast<T*>(p.Qr) + ((tok_base + m) * p.nH + head) * D + 16 * h;
       T* dOr = static_cast<T*>(p.dO) + ((tok_base + m) * p.nH + head) * D + 16 * h;
-      const long toff = (((long)b * p.nH + head) * D) * p.Npad + (m & ~31) + acc_pos(m & 31);
-      T* Qt = static_cast<T*>(p.Qt) + toff;
-      T* dOt = static_cast<T*>(p.dOt) + toff;
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb) {
         store_frag<T>(Qr + cb * 32, qf[cb]);
         store_frag<T>(dOr + cb * 32, dof[cb]);
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const long c = cb * 32 + 8 * q + 4 * h + e;
-            store1(Qt + c * p.Npad, qa[cb][4 * q + e]);
-            store1(dOt + c * p.Npad, da[cb][4 * q + e]);
-          }
       }
     }
   }
@@ -264,32 +253,31 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs p) {
 }
 
 // ---- dK, dV ------------------------------------------------------------------------------------------
-template <typename T, int D, int TQ, bool SHARE> struct DkvLds {
-  static constexpr int kStages = SHARE ? 3 : 2;
-  static constexpr int kRow = D + 16 / sizeof(T);               // Q / dO rows
-  static constexpr int kTRow = TQ + 16 / sizeof(T);             // Q^T / dO^T rows
+template <typename T, int D, int TQ> struct DkvLds {
+  static constexpr int kStages = 3;
+  static constexpr int kRow = D + 16 / sizeof(T);               // Q / dO rows, padded by 16 bytes
   static constexpr int kRElems = TQ * kRow;
-  static constexpr int kTElems = D * kTRow;
-  static constexpr int kStageElems = 2 * kRElems + 2 * kTElems;
+  static constexpr int kStageElems = 2 * kRElems;
   static constexpr size_t kStageBytes = kStageElems * sizeof(T) + 2ul * TQ * sizeof(float);
   // probabilities handed from the dV^T waves to the dK^T waves: [2][4 key blocks][TQ/32] fragment blocks
-  static constexpr size_t kPBytes = SHARE ? 2ul * 4 * (TQ / 32) * kFragBlockElems * sizeof(T) : 0;
+  static constexpr size_t kPBytes = 2ul * 4 * (TQ / 32) * kFragBlockElems * sizeof(T);
   static constexpr size_t kBytes = kStages * kStageBytes + kPBytes;
 };
 
-// Workgroup = 8 waves over 128 keys: waves w and w+4 (one SIMD) own the same 32 keys, held in
-// registers as MFMA column operands.  Wave w forms the probabilities P of a (head, query block)
-// pair and accumulates dV^T += dO^T P; wave w+4 forms dP, dS = P (dP - delta) and accumulates
-// dK^T += Q^T dS.  With SHARE the second wave takes P from LDS, where the first left it one
-// interval earlier (it runs one pair behind, so three stages of staged queries are live); without
-// it (too little LDS: fp32 at the widest latent) it recomputes the scores itself.  Two resident
-// waves per SIMD let one wave's exponentials overlap the other's matrix products.
-template <typename T, int D, int TQ, bool SHARE>
+// Workgroup = 8 waves over 128 keys: waves w and w+4 (one SIMD) own the same 32 keys.  Wave w holds
+// the keys in registers as MFMA column operands, forms the probabilities P of a (head, query block)
+// pair, leaves them in LDS and accumulates dV^T += dO^T P; wave w+4 holds the values, forms dP one
+// interval later, takes P from LDS, and accumulates dK^T += Q^T (P (dP - delta)).  Two resident
+// waves per SIMD let one wave's exponentials overlap the other's matrix products.  The Q and dO rows
+// of a pair are staged once, row-major; the transposed operands Q^T and dO^T are read from the same
+// tiles with transposing LDS loads, so their rows (the channels) come out in the stored channel
+// order of Q and dO (acc order within 32-blocks), which kv_reduce undoes.
+template <typename T, int D, int TQ>
 __global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
   constexpr int CB = D / 32, QBN = TQ / 32, KT = 128, NT = 512;
   constexpr int CE = 16 / sizeof(T);
-  using L = DkvLds<T, D, TQ, SHARE>;
-  constexpr int NS = L::kStages, LAG = SHARE ? 1 : 0;
+  using L = DkvLds<T, D, TQ>;
+  constexpr int NS = L::kStages;
   static_assert(L::kStageBytes % 16 == 0, "stages stay 16-byte aligned");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   T* pbuf = reinterpret_cast<T*>(smem_raw + NS * L::kStageBytes);
@@ -305,20 +293,14 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
   const long tok_base = (long)b * p.Npad;
   const long TP = (long)p.Bsz * p.Npad;
 
-  // column operands of this wave's keys for the whole kernel: the rotated keys for the product
-  // that forms scores, the values for the product that forms dP
-  Frag<T> sop[CB];                                              // keys (SHARE: values in a dK^T wave)
-  Frag<T> vop[SHARE ? 1 : CB];                                  // values of a dK^T wave that also forms scores
+  // column operand of this wave's keys for the whole kernel: the rotated keys in a dV^T wave (it
+  // forms the scores), the values in a dK^T wave (it forms dP)
+  Frag<T> kop[CB];
   {
     const long row = tok_base + (key_ok ? nk : 0);
-    const T* Kg = static_cast<const T*>(p.Kr) + row * D + 16 * h;
-    const T* Vg = static_cast<const T*>(p.Vr) + row * D + 16 * h;
+    const T* src = static_cast<const T*>(k_role ? p.Vr : p.Kr) + row * D + 16 * h;
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-      const T* src = (SHARE && k_role) ? Vg : Kg;
-      sop[cb] = key_ok ? load_frag<T>(src + cb * 32) : zero_frag<T>();
-      if (!SHARE) vop[cb] = key_ok && k_role ? load_frag<T>(Vg + cb * 32) : zero_frag<T>();
-    }
+    for (int cb = 0; cb < CB; ++cb) kop[cb] = key_ok ? load_frag<T>(src + cb * 32) : zero_frag<T>();
   }
   f32x16 acc[CB];                                               // dV^T or dK^T of this wave's keys
 #pragma unroll
@@ -334,35 +316,28 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
   const int n_it = n_heads * n_qb;
   // Query blocks are walked from the last one down: the workgroups of one (sequence, head group),
   // which run on the same XCD at the same time, then all read the same block at the same moment
-  // (with causal masking their ranges start at different blocks but all end at the last), so a
-  // block comes from memory once per XCD instead of once per workgroup.
+  // (with causal masking their ranges start at different blocks but all end at the last).
   auto q_of = [&](int it) { return (qb_first + n_qb - 1 - it % n_qb) * TQ; };
 
-  constexpr int RCH = TQ * D / CE, PT = (RCH + NT - 1) / NT;    // chunks per tensor, per thread
-  constexpr bool FULL = RCH % NT == 0;
-  constexpr int RCPR = D / CE, TCPR = TQ / CE;
   // A staged pair travels global -> registers -> LDS.  PF pairs are in flight in registers, so a
   // round trip to memory is hidden behind PF-1 intervals of work (one interval is shorter than the
   // memory latency).  No load sits behind a branch.
+  constexpr int RCH = TQ * D / CE, PT = (RCH + NT - 1) / NT;    // chunks per tensor, per thread
+  constexpr bool FULL = RCH % NT == 0;
+  constexpr int RCPR = D / CE;
   constexpr int PF = 3;
-  struct Slot { u32x4 q[PT], o[PT], qt[PT], ot[PT]; float stat; } sl[PF];
+  struct Slot { u32x4 q[PT], o[PT]; float stat; } sl[PF];
   auto g_load = [&](Slot& r, int it_raw) {
     const int it = min(it_raw, n_it - 1);                       // past the end: the last pair again, never read
     const int head = head0 + it / n_qb, q0 = q_of(it);
     const T* Qg = static_cast<const T*>(p.Qr) + ((tok_base + q0) * p.nH + head) * D;
     const T* Og = static_cast<const T*>(p.dO) + ((tok_base + q0) * p.nH + head) * D;
-    const long toff = (((long)b * p.nH + head) * D) * p.Npad + q0;
-    const T* Qtg = static_cast<const T*>(p.Qt) + toff;
-    const T* Otg = static_cast<const T*>(p.dOt) + toff;
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int ci = FULL ? threadIdx.x + i * NT : min((int)threadIdx.x + i * NT, RCH - 1);
       const int row = ci / RCPR, cc = ci % RCPR;
       r.q[i] = *reinterpret_cast<const u32x4*>(Qg + (long)row * p.nH * D + cc * CE);
       r.o[i] = *reinterpret_cast<const u32x4*>(Og + (long)row * p.nH * D + cc * CE);
-      const int trow = ci / TCPR, tc = ci % TCPR;
-      r.qt[i] = *reinterpret_cast<const u32x4*>(Qtg + (long)trow * p.Npad + tc * CE);
-      r.ot[i] = *reinterpret_cast<const u32x4*>(Otg + (long)trow * p.Npad + tc * CE);
     }
     // threads 0..255 fetch the log-sum-exp of the block's queries, threads 256.. their delta (TQ of
     // each are kept)
@@ -373,9 +348,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
     unsigned char* sb = smem_raw + (size_t)stage * L::kStageBytes;
     T* qs = reinterpret_cast<T*>(sb);
     T* os = qs + L::kRElems;
-    T* qts = os + L::kRElems;
-    T* ots = qts + L::kTElems;
-    float* stat = reinterpret_cast<float*>(ots + L::kTElems);
+    float* stat = reinterpret_cast<float*>(os + L::kRElems);
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       const int ci = threadIdx.x + i * NT;
@@ -383,35 +356,10 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
       const int row = ci / RCPR, cc = ci % RCPR;
       *reinterpret_cast<u32x4*>(qs + row * L::kRow + cc * CE) = r.q[i];
       *reinterpret_cast<u32x4*>(os + row * L::kRow + cc * CE) = r.o[i];
-      const int trow = ci / TCPR, tc = ci % TCPR;
-      *reinterpret_cast<u32x4*>(qts + trow * L::kTRow + tc * CE) = r.qt[i];
-      *reinterpret_cast<u32x4*>(ots + trow * L::kTRow + tc * CE) = r.ot[i];
     }
     // stored negated: a score block starts from -log-sum-exp, a dP block from -delta
     if (threadIdx.x < TQ) stat[threadIdx.x] = -r.stat;
     else if (threadIdx.x >= 256 && threadIdx.x < 256 + TQ) stat[TQ + threadIdx.x - 256] = -r.stat;
-  };
-
-  // scores of query block qb of a staged pair against this wave's keys, minus log-sum-exp, masked
-  auto scores = [&](const T* qs, const float* stat, int qb, int qfirst, const Frag<T> (&keys)[CB]) -> f32x16 {
-    f32x16 s;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + qb * 32 + 8 * q + 4 * h);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) s[4 * q + e] = l4[e];
-    }
-    const T* qrow = qs + (qb * 32 + lr) * L::kRow + 16 * h;
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) mma32(s, load_frag<T>(qrow + cb * 32), keys[cb]);
-    if (key0 + 31 >= p.N || (p.causal && key0 + 31 > qfirst)) {   // a key past the sequence or after a query
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int mq = qfirst + 8 * (e / 4) + 4 * h + (e % 4);    // query of this register
-        if (nk >= p.N || (p.causal && nk > mq)) s[e] = -INFINITY;
-      }
-    }
-    return s;
   };
 
 #pragma unroll
@@ -419,18 +367,17 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
   s_store(sl[0], 0);
   g_load(sl[0], PF);
   __syncthreads();
-  // one interval: work on the staged pair(s), then move pair t+1 from its register slot to its LDS
-  // stage and refill that slot at once with the pair PF further on
+  // one interval: work on the staged pair, then move pair t+1 from its register slot to its LDS
+  // stage and refill that slot at once with the pair PF further on.  The dK^T waves run one pair
+  // behind the dV^T waves (three stages are live).
   auto interval = [&](auto slot_c, int t) {
     constexpr int S1 = (decltype(slot_c)::value + 1) % PF;      // slot of pair t + 1
-    const int it = k_role ? t - LAG : t;                        // pair this wave works on in this interval
+    const int it = k_role ? t - 1 : t;                          // pair this wave works on in this interval
     if (it >= 0 && it < n_it) {
       const unsigned char* sb = smem_raw + (size_t)(it % NS) * L::kStageBytes;
       const T* qs = reinterpret_cast<const T*>(sb);
       const T* os = qs + L::kRElems;
-      const T* qts = os + L::kRElems;
-      const T* ots = qts + L::kTElems;
-      const float* stat = reinterpret_cast<const float*>(ots + L::kTElems);
+      const float* stat = reinterpret_cast<const float*>(os + L::kRElems);
       const int q0 = q_of(it);
 #pragma unroll
       for (int qb = 0; qb < QBN; ++qb) {
@@ -438,49 +385,47 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
         // all 32 keys of the wave lie after all 32 queries of the block: nothing to do
         if (p.causal && key0 > qfirst + 31) continue;
         T* pblk = pbuf + (long)(((it & 1) * 4 + kb) * QBN + qb) * kFragBlockElems;
-        if (!k_role) {
-          f32x16 s = scores(qs, stat, qb, qfirst, sop);
+        // rows of the block start from -log-sum-exp (scores) or -delta (dP)
+        f32x16 a;
+        const float* st4 = stat + (k_role ? TQ : 0) + qb * 32 + 4 * h;
 #pragma unroll
-          for (int e = 0; e < 16; ++e) s[e] = fast_exp2(s[e]);
-          const Frag<T> pf = to_frag<T>(s);
-          if (SHARE) store_frag_major<T>(pblk, lane, pf);
-          const T* otrow = ots + lr * L::kTRow + qb * 32 + 16 * h;
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 v4 = *reinterpret_cast<const f32x4*>(st4 + 8 * q);
 #pragma unroll
-          for (int cb = 0; cb < CB; ++cb) mma32(acc[cb], load_frag<T>(otrow + cb * 32 * L::kTRow), pf);
-        } else {
-          f32x16 dp;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + TQ + qb * 32 + 8 * q + 4 * h);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) dp[4 * q + e] = d4[e];
-          }
-          const T* orow = os + (qb * 32 + lr) * L::kRow + 16 * h;
-          if (SHARE) {
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) mma32(dp, load_frag<T>(orow + cb * 32), sop[cb]);
-            const Frag<T> pf = load_frag_major<T>(pblk, lane);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) dp[e] *= frag_elem(pf, e);
-          } else {
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) mma32(dp, load_frag<T>(orow + cb * 32), vop[SHARE ? 0 : cb]);
-            const f32x16 s = scores(qs, stat, qb, qfirst, sop);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) dp[e] *= fast_exp2(s[e]);
-          }
-          const Frag<T> dsf = to_frag<T>(dp);
-          const T* qtrow = qts + lr * L::kTRow + qb * 32 + 16 * h;
-#pragma unroll
-          for (int cb = 0; cb < CB; ++cb) mma32(acc[cb], load_frag<T>(qtrow + cb * 32 * L::kTRow), dsf);
+          for (int e = 0; e < 4; ++e) a[4 * q + e] = v4[e];
         }
+        const T* rows = (k_role ? os : qs) + (qb * 32 + lr) * L::kRow + 16 * h;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) mma32(a, load_frag<T>(rows + cb * 32), kop[cb]);
+        Frag<T> bf;                                             // P (dV^T wave) or dS (dK^T wave), k = queries
+        if (!k_role) {
+          if (key0 + 31 >= p.N || (p.causal && key0 + 31 > qfirst)) {   // a key past the sequence or after a query
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int mq = qfirst + 8 * (e / 4) + 4 * h + (e % 4);    // query of this register
+              if (nk >= p.N || (p.causal && nk > mq)) a[e] = -INFINITY;
+            }
+          }
+#pragma unroll
+          for (int e = 0; e < 16; ++e) a[e] = fast_exp2(a[e]);
+          bf = to_frag<T>(a);
+          store_frag_major<T>(pblk, lane, bf);
+        } else {
+          const Frag<T> pf = load_frag_major<T>(pblk, lane);
+#pragma unroll
+          for (int e = 0; e < 16; ++e) a[e] *= frag_elem(pf, e);
+          bf = to_frag<T>(a);
+        }
+        const T* tile = k_role ? qs : os;                       // dK^T += Q^T dS,  dV^T += dO^T P
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) mma32(acc[cb], load_frag_tr(tile, L::kRow, qb * 32, cb * 32, lane), bf);
       }
     }
     s_store(sl[S1], (t + 1) % NS);
     g_load(sl[S1], t + 1 + PF);
     __syncthreads();
   };
-  const int n_int = n_it + LAG;
+  const int n_int = n_it + 1;
   int t = 0;
   for (; t + PF <= n_int; t += PF) {
     interval(std::integral_constant<int, 0>{}, t);
@@ -490,6 +435,7 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
   if (t < n_int) interval(std::integral_constant<int, 0>{}, t);
   if (t + 1 < n_int) interval(std::integral_constant<int, 1>{}, t + 1);
 
+  // rows of the accumulators are stored channel positions: position 16h'+4q'+r of a 32-block
   if (key_ok) {
     float* dst = (k_role ? p.dKp : p.dVp) + ((long)hg * TP + tok_base + nk) * D + 4 * h;
 #pragma unroll
@@ -513,8 +459,11 @@ __global__ __launch_bounds__(256) void kv_reduce_kernel(KvReduceArgs a) {
   const int k = (int)(idx % quads);
   const int n = (int)(tp % a.Npad);
   f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
+  // the partials hold channel quad k at its stored (acc-order) position inside its 32-block
+  const int c32 = (4 * k) % 32;
+  const int spos = (4 * k) / 32 * 32 + 16 * ((c32 / 4) % 2) + 4 * (c32 / 8);
   for (int g = 0; g < a.n_hg; ++g) {
-    const long off = ((long)g * TP + tp) * a.D + 4 * k;
+    const long off = ((long)g * TP + tp) * a.D + spos;
     const f32x4 x = *reinterpret_cast<const f32x4*>(a.dKp + off);
     const f32x4 y = *reinterpret_cast<const f32x4*>(a.dVp + off);
 #pragma unroll
@@ -569,12 +518,12 @@ hipError_t launch_bwd_dq(int dtype, const BwdArgs& a, hipStream_t s) {
   return hipErrorInvalidValue;
 }
 
-template <typename T, int D, int TQ, bool SHARE>
+template <typename T, int D, int TQ>
 static hipError_t dkv_one(const BwdArgs& a, hipStream_t s) {
   dim3 grid(a.n_hg * a.Bsz, (a.Npad + 127) / 128);
-  const size_t smem = DkvLds<T, D, TQ, SHARE>::kBytes;
-  static_assert(DkvLds<T, D, TQ, SHARE>::kBytes <= 160 * 1024, "fits the LDS of a compute unit");
-  auto kern = bwd_dkv_kernel<T, D, TQ, SHARE>;
+  const size_t smem = DkvLds<T, D, TQ>::kBytes;
+  static_assert(DkvLds<T, D, TQ>::kBytes <= 160 * 1024, "fits the LDS of a compute unit");
+  auto kern = bwd_dkv_kernel<T, D, TQ>;
   static LdsOnce lds_once;
   if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
   hipLaunchKernelGGL(kern, grid, dim3(512), smem, s, a);
@@ -584,15 +533,15 @@ static hipError_t dkv_one(const BwdArgs& a, hipStream_t s) {
 hipError_t launch_bwd_dkv(int dtype, const BwdArgs& a, hipStream_t s) {
   if (dtype == 0) {
     switch (a.D) {
-      case 32: return dkv_one<float, 32, 32, true>(a, s);
-      case 64: return dkv_one<float, 64, 32, true>(a, s);
-      case 128: return dkv_one<float, 128, 32, false>(a, s);
+      case 32: return dkv_one<float, 32, 32>(a, s);
+      case 64: return dkv_one<float, 64, 32>(a, s);
+      case 128: return dkv_one<float, 128, 32>(a, s);
     }
   } else {
     switch (a.D) {
-      case 32: return dkv_one<bf16, 32, 64, true>(a, s);
-      case 64: return dkv_one<bf16, 64, 32, true>(a, s);
-      case 128: return dkv_one<bf16, 128, 32, true>(a, s);
+      case 32: return dkv_one<bf16, 32, 64>(a, s);
+      case 64: return dkv_one<bf16, 64, 64>(a, s);
+      case 128: return dkv_one<bf16, 128, 64>(a, s);
     }
   }
   return hipErrorInvalidValue;

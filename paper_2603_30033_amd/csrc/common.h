@@ -172,6 +172,37 @@ template <> __device__ __forceinline__ void store_frag_major<bf16>(bf16* block, 
   q[64] = f.v[1];
 }
 
+// Transposed fragment from a row-major LDS tile: the operand row of this lane is tile COLUMN
+// col0 + lane%32, and its 16 contraction elements are tile rows row0 + 8q+4h+r (acc order, q and r
+// in 0..3) of that column.  bf16: four transposing LDS reads (each hands a lane four consecutive
+// rows of its column: within 16 lanes, lane i supplies the address of row i/4, columns 4(i%4)..+3,
+// and receives column i of the four rows); fp32: sixteen 4-byte reads.  `stride` in elements.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ Frag<bf16> load_frag_tr(const bf16* tile, int stride, int row0, int col0, int lane) {
+  const int h = lane / 32, i = lane % 16;
+  const bf16* base = tile + (row0 + 4 * h + i / 4) * stride + col0 + (lane & 16) + 4 * (i % 4);
+  Frag<bf16> f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    auto* lp = (__attribute__((address_space(3))) s16x4*)(base + 8 * q * stride);
+    const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(lp);
+    const bf16x4 b = __builtin_bit_cast(bf16x4, v);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) f.v[q / 2][(q % 2) * 4 + r] = b[r];
+  }
+  return f;
+}
+__device__ __forceinline__ Frag<float> load_frag_tr(const float* tile, int stride, int row0, int col0, int lane) {
+  const int h = lane / 32;
+  const float* base = tile + (row0 + 4 * h) * stride + col0 + lane % 32;
+  Frag<float> f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) f.v[q][r] = base[(8 * q + r) * stride];
+  return f;
+}
+
 // four consecutive accumulator registers (rows 8q+4h .. +3) -> 4 elements of T at p (natural order)
 __device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
   *reinterpret_cast<f32x4*>(p) = f32x4{a, b, c, d};

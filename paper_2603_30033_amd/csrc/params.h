@@ -105,8 +105,6 @@ struct BwdArgs {
   float* delta;        // [B][nH][Npad]  sum_c dO O
   void* Qr;            // [TP][nH][D] rotated, scaled per-head queries (acc order in c)
   void* dO;            // [TP][nH][D] (acc order in c)
-  void* Qt;            // [B][nH][D][Npad] transposes of the two, n in acc order within 32-blocks
-  void* dOt;
   void* dQ;            // [TP][nH][D] gradient of the unrotated per-head query / sqrt-free scale, acc order in c
   void* dQt;           // [nH*D][TP] the same, c natural, tokens natural
   float* dKp;          // [n_hg][TP][D] per-head-group partial gradients of the rotated keys / values
