@@ -81,8 +81,7 @@ PrefillWs carve_prefill(const tucker_attn_ctx* c, void* ws, int B, int N) {
 struct BackwardWs {
   PrefillWs f;
   float *lse, *delta, *dKp, *dVp, *dG, *dGt, *part;
-  void *Vr, *Krt, *Ut2T, *Gtil_t, *G2, *Wb, *dZ, *Qr, *dO, *dQ, *dQt, *dLat;
-  void *Xt, *dYt, *dLat_t, *Zt, *Qlat_t, *dZt, *Ot;
+  void *Vr, *Krt, *Ut2T, *Gtil_t, *G2, *Wb, *dZ, *Qr, *dO, *dQ, *dLat;
   int LW;            // width of the latent-gradient rows: R2 + D (shared latent) or R2 + 2 D
   int hpg, n_hg;     // heads per group / number of groups of the key-value gradient kernel
   int ks_w, ks_u, ks_g;   // contraction splits of the weight-gradient products
@@ -124,24 +123,17 @@ BackwardWs carve_backward(const tucker_attn_ctx* c, void* ws, int B, int N) {
   w.Qr = cv.take<char>(TP * nHD * es);
   w.dO = cv.take<char>(TP * nHD * es);
   w.dQ = cv.take<char>(TP * nHD * es);
-  w.dQt = cv.take<char>(TP * nHD * es);
   w.dKp = cv.take<float>((size_t)w.n_hg * TP * c->D * 4);
   w.dVp = cv.take<float>((size_t)w.n_hg * TP * c->D * 4);
   w.dLat = cv.take<char>(TP * w.LW * es);
-  w.Xt = cv.take<char>((size_t)c->dp * TP * es);
-  w.dYt = cv.take<char>((size_t)c->dp * TP * es);
-  w.dLat_t = cv.take<char>((size_t)w.LW * TP * es);
-  w.Zt = cv.take<char>((size_t)c->RT2 * TP * es);
-  w.Qlat_t = cv.take<char>((size_t)c->R2 * TP * es);
-  w.dZt = cv.take<char>((size_t)c->RT2 * TP * es);
-  w.Ot = cv.take<char>(nHD * TP * es);
   w.dG = cv.take<float>((size_t)c->R2 * nHD * 4);
   w.dGt = cv.take<float>((size_t)c->RT2 * nHD * 4);
   const long mt = (f.d_model + 127) / 128;
-  w.ks_w = grad_ksplit(mt * ((w.LW + 63) / 64), (long)TP);
-  w.ks_u = grad_ksplit(mt * ((c->RT2 + 63) / 64), (long)TP);
+  auto col_tiles = [&](long cols) { return f.dtype == TUCKER_ATTN_BF16 && cols % 128 == 0 ? cols / 128 : (cols + 63) / 64; };
+  w.ks_w = grad_ksplit(mt * col_tiles(w.LW), (long)TP);
+  w.ks_u = grad_ksplit(mt * col_tiles(c->RT2), (long)TP);
   const int rmax = c->R2 > c->RT2 ? c->R2 : c->RT2;
-  w.ks_g = grad_ksplit(((rmax + 127) / 128) * (long)((nHD + 63) / 64), (long)TP);
+  w.ks_g = grad_ksplit(((rmax + 127) / 128) * col_tiles((long)nHD), (long)TP);
   size_t part = (size_t)w.ks_w * w.LW * pad32(f.d_model);
   const size_t p2 = (size_t)w.ks_u * c->RT2 * pad32(f.d_model), p3 = (size_t)w.ks_g * nHD * rmax;
   if (p2 > part) part = p2;
@@ -513,7 +505,7 @@ int tucker_attn_backward(tucker_attn_ctx* c, const tucker_attn_weights* w, const
   std::memset(&a, 0, sizeof(a));
   a.Qlat = ws.f.Qlat; a.Gt = ws.f.Gt; a.dZ = ws.dZ; a.Gtil_t = ws.Gtil_t; a.Kr = ws.f.Kr; a.Vr = ws.Vr; a.Krt = ws.Krt;
   a.O = ws.f.O; a.lse = ws.lse; a.delta = ws.delta; a.Qr = ws.Qr; a.dO = ws.dO;
-  a.dQ = ws.dQ; a.dQt = ws.dQt; a.dKp = ws.dKp; a.dVp = ws.dVp; a.rope = c->rope; a.rope_ld = f.max_positions;
+  a.dQ = ws.dQ; a.dKp = ws.dKp; a.dVp = ws.dVp; a.rope = c->rope; a.rope_ld = f.max_positions;
   a.Bsz = B; a.N = N; a.Npad = Npad; a.nH = f.n_heads; a.R2 = c->R2; a.RT2 = c->RT2; a.D = c->D;
   a.causal = f.causal; a.pos0 = pos0; a.hpg = ws.hpg; a.n_hg = ws.n_hg;
   if (launch_bwd_dq(f.dtype, a, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
@@ -554,55 +546,44 @@ int tucker_attn_backward(tucker_attn_ctx* c, const tucker_attn_weights* w, const
     rec.after("grad_x");
   }
 
-  // ---- token-minor copies for the products that contract over tokens ------------------------------------------
-  auto transpose = [&](const void* src, long ld, int cols, int cols_pad, int src_padded, int unperm, void* dst) {
-    TransposeArgs t;
+  // ---- products over tokens: out[m][n] = sum_t A[t][m] B[t][n], operands token-major as they are -----------------
+  auto over_tokens = [&](const void* At, long lda, int a_padded, int M, int perm_m, const void* Bt, long ldb, int cols,
+                         int perm_n, int ksplit, const GemmArgs::Out3 (&outs)[3]) {
+    TnArgs t;
     std::memset(&t, 0, sizeof(t));
-    t.src = src; t.ld = ld; t.cols = cols; t.cols_pad = cols_pad;
-    t.Bsz = B; t.N = N; t.Npad = Npad; t.src_padded = src_padded; t.unperm = unperm; t.dst = dst;
-    return launch_transpose(f.dtype, t, s);
-  };
-  if (transpose(X, f.d_model, f.d_model, c->dp, 0, 0, ws.Xt) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  if (transpose(dY, f.d_model, f.d_model, c->dp, 0, 0, ws.dYt) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  if (transpose(ws.dLat, LW, LW, LW, 1, 0, ws.dLat_t) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  if (transpose(ws.f.Z, c->RT2, c->RT2, c->RT2, 1, 0, ws.Zt) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  if (transpose(ws.f.Qlat, c->R2, c->R2, c->R2, 1, 1, ws.Qlat_t) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  if (transpose(ws.dZ, c->RT2, c->RT2, c->RT2, 1, 0, ws.dZt) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  if (transpose(ws.f.O, nHD, nHD, nHD, 1, 1, ws.Ot) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("token_minor_copies");
-
-  // ---- products over tokens: out[m][n] = sum_t At[m][t] Bt[n][t] -----------------------------------------------
-  auto over_tokens = [&](const void* At, int M, const void* Bt, int rows, int ksplit, float scale,
-                         const GemmArgs::Out3 (&outs)[3]) {
-    GemmArgs g;
-    std::memset(&g, 0, sizeof(g));
-    g.A = At; g.lda = TP; g.M = M;
-    g.Bsrc = Bt; g.ldb = TP; g.K = (int)TP;
-    g.Bsz = 1; g.N = rows; g.Npad = rows; g.src_padded = 1;
-    g.epi = 3; g.ksplit = ksplit; g.part = ws.part; g.out_scale = scale;
-    for (int u = 0; u < 3; ++u) g.out3[u] = outs[u];
-    return launch_gemm(f.dtype, g, 64, s);
+    t.At = At; t.lda = lda; t.a_padded = a_padded; t.Bt = Bt; t.ldb = ldb; t.b_padded = 1;
+    t.Bsz = B; t.N = N; t.Npad = Npad;
+    t.g.M = M; t.g.Bsz = 1; t.g.N = cols; t.g.Npad = cols;
+    t.g.epi = 3; t.g.ksplit = ksplit; t.g.part = ws.part; t.g.out_scale = 1.f;
+    t.g.perm_m = perm_m; t.g.perm_n = perm_n;
+    for (int u = 0; u < 3; ++u) t.g.out3[u] = outs[u];
+    return launch_gemm_tn(f.dtype, t, s);
   };
   {
     const GemmArgs::Out3 o[3] = {{gr->dU2, 0, f.r2, f.r2},
                                  {gr->dU3, c->R2, c->R2 + f.r3, f.r3},
                                  {f.shared_kv ? nullptr : gr->dUt3, c->R2 + c->D, c->R2 + c->D + f.rt3, f.rt3}};
-    if (over_tokens(ws.Xt, f.d_model, ws.dLat_t, LW, ws.ks_w, 1.f, o) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    if (over_tokens(X, f.d_model, 0, f.d_model, 0, ws.dLat, LW, LW, 0, ws.ks_w, o) != hipSuccess)
+      return TUCKER_ATTN_HIP_ERROR;
     rec.after("grad_u2_u3_ut3");
   }
   {
     const GemmArgs::Out3 o[3] = {{gr->dUt2, 0, f.rt2, f.rt2}, {nullptr, 0, 0, 0}, {nullptr, 0, 0, 0}};
-    if (over_tokens(ws.dYt, f.d_model, ws.Zt, c->RT2, ws.ks_u, 1.f, o) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    if (over_tokens(dY, f.d_model, 0, f.d_model, 0, ws.f.Z, c->RT2, c->RT2, 0, ws.ks_u, o) != hipSuccess)
+      return TUCKER_ATTN_HIP_ERROR;
     rec.after("grad_ut2");
   }
   {
+    // Qlat holds its columns, and dQ / O their channels, in acc order: undone when the result is stored
     const GemmArgs::Out3 o[3] = {{ws.dG, 0, nHD, nHD}, {nullptr, 0, 0, 0}, {nullptr, 0, 0, 0}};
-    if (over_tokens(ws.Qlat_t, c->R2, ws.dQt, nHD, ws.ks_g, 1.f, o) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    if (over_tokens(ws.f.Qlat, c->R2, 1, c->R2, 1, ws.dQ, nHD, nHD, 1, ws.ks_g, o) != hipSuccess)
+      return TUCKER_ATTN_HIP_ERROR;
     rec.after("grad_core_mixed");
   }
   {
     const GemmArgs::Out3 o[3] = {{ws.dGt, 0, nHD, nHD}, {nullptr, 0, 0, 0}, {nullptr, 0, 0, 0}};
-    if (over_tokens(ws.dZt, c->RT2, ws.Ot, nHD, ws.ks_g, 1.f, o) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    if (over_tokens(ws.dZ, c->RT2, 1, c->RT2, 0, ws.f.O, nHD, nHD, 1, ws.ks_g, o) != hipSuccess)
+      return TUCKER_ATTN_HIP_ERROR;
     rec.after("grad_core_mixed_post");
   }
 

@@ -11,9 +11,7 @@
 // Two kernels, neither with atomics:
 //   bwd_dq   one wave = 32 queries of one head, walks the key tiles like the forward kernel:
 //            builds Q_i and dO_i in a prologue from the latent query and dZ (and leaves copies of
-//            both for the second kernel), accumulates dQ_i, removes the
-//            rotation and stores it (plain for the latent-query gradient, transposed for the
-//            gradient of the core).
+//            both for the second kernel), accumulates dQ_i, removes the rotation and stores it.
 //   bwd_dkv  a pair of waves = 32 keys kept in registers as operands, walks (head, query block)
 //            pairs staged in LDS; one wave of the pair accumulates dV^T, the other dK^T; heads are
 //            split into groups over workgroups, each writing a partial sum that kv_reduce adds up
@@ -236,19 +234,12 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs p) {
     __syncthreads();
   }
 
-  // ---- epilogue: remove the rotation, store plain and transposed -----------------------------------
+  // ---- epilogue: remove the rotation, store -----------------------------------------------------------
   if (p.rope != nullptr) rotate_blocks<CB>(dq, p.rope, p.rope_ld, p.pos0 + min(m, p.N - 1), h, -1.f);
   if (head_ok) {
     T* dQ = static_cast<T*>(p.dQ) + ((tok_base + m) * p.nH + head) * D + 16 * h;
-    T* dQt = static_cast<T*>(p.dQt) + ((long)head * D) * TP + tok_base + m;
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-      store_frag<T>(dQ + cb * 32, to_frag<T>(dq[cb]));
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) store1(dQt + (long)(cb * 32 + 8 * q + 4 * h + e) * TP, dq[cb][4 * q + e]);
-    }
+    for (int cb = 0; cb < CB; ++cb) store_frag<T>(dQ + cb * 32, to_frag<T>(dq[cb]));
   }
 }
 

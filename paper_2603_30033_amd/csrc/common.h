@@ -35,6 +35,9 @@ __host__ __device__ constexpr int pad64(int x) { return (x + 63) / 64 * 64; }
 // position of contraction index x (0..31) inside an acc-ordered 32-block
 __host__ __device__ constexpr int acc_pos(int x) { return 16 * ((x >> 2) & 1) + 4 * (x >> 3) + (x & 3); }
 
+// natural index of the element stored at position p of an acc-ordered 32-block (inverse of acc_pos)
+__host__ __device__ constexpr int acc_index(int p) { return 8 * ((p >> 2) & 3) + 4 * (p >> 4) + (p & 3); }
+
 template <typename T> struct Frag;
 template <> struct Frag<float> { f32x4 v[4]; };      // 16 fp32
 template <> struct Frag<bf16> { bf16x8 v[2]; };      // 16 bf16

@@ -199,16 +199,19 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& g, f32x16 acc, in
       if (c < g.M) store4(row + c, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
     }
   } else if (g.epi == 3) {                                      // ---- fp32 matrix, column ranges routed
+    // a row or column that sits at an acc-order position of its 32-block is stored at its natural index
+    const int nn = g.perm_n ? (tp & ~31) + acc_index(tp & 31) : tp;
 #pragma unroll
     for (int u = 0; u < 3; ++u) {
       const GemmArgs::Out3& o = g.out3[u];
-      if (o.ptr == nullptr || tp < o.n0 || tp >= o.n1) continue;
+      if (o.ptr == nullptr || nn < o.n0 || nn >= o.n1) continue;
 #pragma unroll
       for (int q = 0; q < 4; ++q)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int m = m0 + 8 * q + 4 * h + e;
-          if (m < g.M) o.ptr[(long)m * o.ld + (tp - o.n0)] = g.out_scale * acc[4 * q + e];
+          const int mp = 8 * q + 4 * h + e;
+          const int m = m0 + (g.perm_m ? acc_index(mp) : mp);
+          if (m < g.M) o.ptr[(long)m * o.ld + (nn - o.n0)] = g.out_scale * acc[4 * q + e];
         }
     }
   } else {                                                      // ---- Y, caller's [B][N][d]
@@ -467,6 +470,19 @@ static hipError_t launch_one(const GemmArgs& a, int m_rows, hipStream_t s) {
   if (e != hipSuccess || a.ksplit <= 1) return e;
   dim3 rgrid((m_rows + 31) / 32, (TP + 31) / 32);
   hipLaunchKernelGGL(splitk_reduce_kernel<T>, rgrid, dim3(64), 0, s, a);
+  return hipGetLastError();
+}
+
+// sum of a.ksplit partial tiles in a.part, then the epilogue (also used by the token-contracting
+// products of gemm_tn.hip, which always go through partial tiles)
+hipError_t launch_splitk_reduce(int dtype, const GemmArgs& a, hipStream_t s) {
+  const int m_rows = (a.epi == 0) ? a.R2 + (a.shared_kv ? 1 : 2) * a.D : a.M;
+  const int TP = a.Bsz * a.Npad;
+  dim3 rgrid((m_rows + 31) / 32, (TP + 31) / 32);
+  if (dtype == 0)
+    hipLaunchKernelGGL(splitk_reduce_kernel<float>, rgrid, dim3(64), 0, s, a);
+  else
+    hipLaunchKernelGGL(splitk_reduce_kernel<bf16>, rgrid, dim3(64), 0, s, a);
   return hipGetLastError();
 }
 

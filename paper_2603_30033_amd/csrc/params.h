@@ -75,6 +75,16 @@ struct GemmArgs {
   // ptr[m * ld + (n - n0)] (up to three destinations; ptr null = unused)
   struct Out3 { float* ptr; int n0, n1; long ld; } out3[3];
   float out_scale;
+  int perm_m, perm_n;   // 1: rows / columns of the product are in acc order within 32-blocks; stored natural
+};
+
+// out[m][n] = sum over tokens t of At[t][m] * Bt[t][n]; both operands token-major.  g carries the
+// output side as for epilogue 3 (M, Bsz = 1, N = Npad = number of columns, ksplit, part, out3, ...).
+struct TnArgs {
+  GemmArgs g;
+  const void* At; long lda; int a_padded;   // padded: row of token (b, n) is b*Npad + n, else b*N + n
+  const void* Bt; long ldb; int b_padded;
+  int Bsz, N, Npad;
 };
 
 // ---- prefill attention ---------------------------------------------------------------------
@@ -106,7 +116,6 @@ struct BwdArgs {
   void* Qr;            // [TP][nH][D] rotated, scaled per-head queries (acc order in c)
   void* dO;            // [TP][nH][D] (acc order in c)
   void* dQ;            // [TP][nH][D] gradient of the unrotated per-head query / sqrt-free scale, acc order in c
-  void* dQt;           // [nH*D][TP] the same, c natural, tokens natural
   float* dKp;          // [n_hg][TP][D] per-head-group partial gradients of the rotated keys / values
   float* dVp;
   const float4* rope;
@@ -123,16 +132,6 @@ struct KvReduceArgs {
   void* dLat; long ld; int colK, colV;
   const float4* rope; int rope_ld;
   int Bsz, N, Npad, D, n_hg, pos0, shared_kv;
-};
-
-// out[c][tp] = src[row(tp)][c] (zero where the token or the column does not exist)
-struct TransposeArgs {
-  const void* src; long ld;
-  int cols;            // source columns to move; output rows cols .. cols_pad-1 are zero filled
-  int cols_pad;
-  int Bsz, N, Npad, src_padded;
-  int unperm;          // 1: source columns are stored in acc order within 32-blocks; output rows natural
-  void* dst;           // [cols_pad][TP]
 };
 
 // dC[a][b][c] = scale * sum_i U1[i][a] dG[b][i*D + c];  dU1[i][a] = scale * sum_bc dG[b][i*D+c] C[a][b][c]
@@ -185,11 +184,12 @@ hipError_t launch_prep(int dtype, const PrepArgs& a, hipStream_t s);
 bool out_proj_supported(int dtype, const GemmArgs& a);
 hipError_t launch_out_proj(int dtype, const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm(int dtype, const GemmArgs& a, int tile_n, hipStream_t s);
+hipError_t launch_splitk_reduce(int dtype, const GemmArgs& a, hipStream_t s);
+hipError_t launch_gemm_tn(int dtype, const TnArgs& a, hipStream_t s);
 hipError_t launch_attn_prefill(int dtype, const AttnArgs& a, hipStream_t s);
 hipError_t launch_bwd_dq(int dtype, const BwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_dkv(int dtype, const BwdArgs& a, hipStream_t s);
 hipError_t launch_kv_reduce(int dtype, const KvReduceArgs& a, hipStream_t s);
-hipError_t launch_transpose(int dtype, const TransposeArgs& a, hipStream_t s);
 hipError_t launch_core_grad(int dtype, const CoreGradArgs& a, hipStream_t s);
 hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s);

@@ -151,3 +151,14 @@ def test_backward_argument_errors():
         assert ta.tucker_attn_backward(layer.ctx, layer.weights, X, X, dX, g2, 0, ws, check=False) == -1
         assert ta.tucker_attn_backward(layer.ctx, layer.weights, X, X, dX, grads, 0, ws[:1024], check=False) == -3
         torch.cuda.synchronize()
+
+
+def test_backward_gpt2_full_size():
+    # the GPT-2-small-shaped workload as the benchmark launches it (B=8, N=1024), every gradient
+    run_case(wl.WORKLOADS["gpt2_small"])
+
+
+def test_backward_llama_full_size():
+    # the LLaMA-7B-shaped workload at the size and launch configuration bench.py times (B=2, N=4096):
+    # every gradient against the oracle (about a minute of fp64 work on the host)
+    run_case(wl.WORKLOADS["llama7b_n4096"])
