@@ -24,7 +24,10 @@ template <typename T, int COLS> struct TnStager {
   static constexpr int kChunks = kTS * kCPR;
   static constexpr int kPerThread = kChunks / 256;
   static_assert(kChunks % 256 == 0, "slice must fill all threads");
-  static constexpr int kRow = COLS + CE;                         // LDS row, padded by 16 bytes
+  // LDS row padded by 64 bytes: the four rows that one transposing read of 16 lanes touches (32
+  // bytes each, and the 32 bytes next to them for the neighbouring 16 lanes) then fall into
+  // disjoint banks
+  static constexpr int kRow = COLS + 64 / (int)sizeof(T);
   static constexpr uint32_t kNone = 0x80000000u;
   struct Regs { u32x4 r[kPerThread]; };
   uint32_t off[kPerThread];                                      // byte offset inside a slice, or kNone
