@@ -68,8 +68,6 @@ template <typename T, int D, int BC> struct DecLds {
   static constexpr size_t kBytes = 2ul * kStageElems * sizeof(T);
 };
 
-__device__ __forceinline__ float lds_elem(const float* p) { return *p; }
-__device__ __forceinline__ bf16 lds_elem(const bf16* p) { return *p; }
 
 // SH: shared key-value latent (one unrotated cache; keys rotated as a tile is staged)
 template <typename T, int D, int BC, int HB, bool SH>
@@ -276,17 +274,11 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeArgs p) {
       for (int e = 0; e < 16; ++e) oacc[hb][e] *= alpha;
     }
     // O^T[c][head] += V^T[c][n] P^T[n][head] for this wave's value block: lane = channel c,
-    // half h gathers keys 8q+4h+r of each 32-key block from the row-major V tile
+    // half h takes keys 8q+4h+r of each 32-key block from the row-major V tile (transposing LDS loads)
     if (has_c) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        const T* col = vs + (nb * 32 + 4 * h) * L::kRowElems + cbw * 32 + lr;
-        f32x16 tmp;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) tmp[4 * q + r] = to_f32(lds_elem(col + (8 * q + r) * L::kRowElems));
-        Frag<T> vf = to_frag<T>(tmp);                             // exact: values are already T
+        const Frag<T> vf = load_frag_tr(vs, L::kRowElems, nb * 32, cbw * 32, lane);
 #pragma unroll
         for (int hb = 0; hb < HB; ++hb) mma32(oacc[hb], vf, pf[hb][nb]);
       }
