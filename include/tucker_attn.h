@@ -19,7 +19,8 @@
  *   - "device" pointers are HIP device memory of the GPU that was current at
  *     tucker_attn_create; "host" pointers are ordinary process memory.
  *   - The caller owns every buffer it passes (inputs, outputs, caches, workspace); the
- *     library keeps no pointer after a call returns.  The context owns only host state
+ *     library keeps no pointer after a call returns (one documented exception:
+ *     tucker_attn_prepare_weights).  The context owns only host state
  *     and one device table of rotation cosines/sines allocated in create.
  *   - forward/decode only enqueue work on the given HIP stream and return; results are
  *     valid once the caller has synchronised that stream.  Calls that share a
@@ -184,6 +185,23 @@ int tucker_attn_backward(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
                          const void *X, const void *dY, void *dX, const tucker_attn_grads *grads,
                          int32_t B, int32_t N, int32_t pos0, int32_t forward_state,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Weights that stay fixed over many calls (serving): prepare their operand-layout copies once
+ * (the head-mixed cores G_i = sum_a U1[i,a] C[a] of Section "KV Caching" and the transposed, padded
+ * factor matrices, step one of every forward / decode call) into a caller-owned device buffer, and
+ * every later forward / decode / backward call of this context skips that step.
+ *   prepared   device, >= tucker_attn_prepared_weights_bytes(ctx) bytes, 256-byte aligned
+ * Exception to the ownership rule above: the context keeps the pointer `prepared` and the eight
+ * weight pointers of `w` until tucker_attn_release_weights or tucker_attn_destroy; the caller keeps
+ * the buffer alive and unmodified, orders the prepare call before the calls that use it (same
+ * stream, or synchronised), and passes the same weight pointers to those calls (others are refused
+ * with TUCKER_ATTN_INVALID_ARG).  After the weights' values change, prepare again or release.
+ */
+size_t tucker_attn_prepared_weights_bytes(const tucker_attn_ctx *ctx);
+int tucker_attn_prepare_weights(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
+                                void *prepared, size_t prepared_bytes, void *hip_stream);
+int tucker_attn_release_weights(tucker_attn_ctx *ctx);
 
 /*
  * Optional per-kernel timing for benchmarks.  While enabled, forward/backward/decode bracket every

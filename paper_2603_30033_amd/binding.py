@@ -20,6 +20,7 @@ EXPORTED = [
     "tucker_attn_create", "tucker_attn_destroy", "tucker_attn_workspace_bytes",
     "tucker_attn_decode_workspace_bytes", "tucker_attn_forward", "tucker_attn_decode",
     "tucker_attn_backward_workspace_bytes", "tucker_attn_backward",
+    "tucker_attn_prepared_weights_bytes", "tucker_attn_prepare_weights", "tucker_attn_release_weights",
     "tucker_attn_profile_enable", "tucker_attn_profile_read", "tucker_attn_status_string",
 ]
 
@@ -84,6 +85,12 @@ def load_library() -> C.CDLL:
                                          C.POINTER(tucker_attn_grads), C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_void_p, C.c_size_t, C.c_void_p]
     lib.tucker_attn_backward.restype = C.c_int
+    lib.tucker_attn_prepared_weights_bytes.argtypes = [ctx_p]
+    lib.tucker_attn_prepared_weights_bytes.restype = C.c_size_t
+    lib.tucker_attn_prepare_weights.argtypes = [ctx_p, C.POINTER(tucker_attn_weights), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.tucker_attn_prepare_weights.restype = C.c_int
+    lib.tucker_attn_release_weights.argtypes = [ctx_p]
+    lib.tucker_attn_release_weights.restype = C.c_int
     lib.tucker_attn_profile_enable.argtypes = [ctx_p, C.c_int32]
     lib.tucker_attn_profile_enable.restype = C.c_int
     lib.tucker_attn_profile_read.argtypes = [ctx_p, C.POINTER(C.c_char_p), C.POINTER(C.c_float), C.c_int32]
@@ -196,6 +203,25 @@ def tucker_attn_backward(ctx: int, weights: Dict, X, dY, dX, grads: Dict, pos0: 
     if check:
         _check(st, "tucker_attn_backward")
     return st
+
+
+def tucker_attn_prepared_weights_bytes(ctx: int) -> int:
+    return int(load_library().tucker_attn_prepared_weights_bytes(ctx))
+
+
+def tucker_attn_prepare_weights(ctx: int, weights: Dict, prepared, stream=None, check: bool = True) -> int:
+    """prepared: device uint8 tensor of at least tucker_attn_prepared_weights_bytes bytes; the caller keeps it
+    (and the weight tensors) alive until tucker_attn_release_weights."""
+    ws = _weights_struct(weights)
+    st = load_library().tucker_attn_prepare_weights(ctx, C.byref(ws), _ptr(prepared),
+                                                    0 if prepared is None else prepared.numel(), _stream_ptr(stream))
+    if check:
+        _check(st, "tucker_attn_prepare_weights")
+    return st
+
+
+def tucker_attn_release_weights(ctx: int) -> None:
+    _check(load_library().tucker_attn_release_weights(ctx), "tucker_attn_release_weights")
 
 
 def tucker_attn_profile_enable(ctx: int, on: bool) -> None:

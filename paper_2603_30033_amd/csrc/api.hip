@@ -31,6 +31,10 @@ struct tucker_attn_ctx {
   const char* names[kMaxKernels];
   hipEvent_t ev[kMaxKernels + 1];
   bool ev_created;
+  // prepared weights (tucker_attn_prepare_weights): caller-owned buffer in the layout of
+  // carve_weights, and the weight pointers it was made from
+  void* prepared;
+  tucker_attn_weights prepared_from;
 };
 
 namespace {
@@ -61,6 +65,26 @@ void carve_weights(const tucker_attn_ctx* c, Carver& cv, void*& Gt, void*& Gtil2
   Gtil2 = cv.take<char>((size_t)c->RT2 * f.n_heads * c->D * c->es);
   Wcat = cv.take<char>((size_t)(c->R2 + 2 * c->D) * c->dp * c->es);
   Ut2p = cv.take<char>((size_t)c->dp * c->RT2 * c->es);
+}
+
+size_t prepared_bytes(const tucker_attn_ctx* c) {
+  Carver cv{nullptr, 0};
+  void *a, *b, *d, *e;
+  carve_weights(c, cv, a, b, d, e);
+  return cv.off;
+}
+
+// The operand-layout copies of the weights: a piece of the call's workspace, or the caller's
+// prepared buffer when one is registered (then no preparation kernel runs).
+template <typename W> void use_prepared(const tucker_attn_ctx* c, W& w) {
+  if (!c->prepared) return;
+  Carver cv{static_cast<char*>(c->prepared), 0};
+  carve_weights(c, cv, w.Gt, w.Gtil2, w.Wcat, w.Ut2p);
+}
+
+bool same_weights(const tucker_attn_weights& a, const tucker_attn_weights& b) {
+  return a.C == b.C && a.U1 == b.U1 && a.U2 == b.U2 && a.U3 == b.U3 && a.Ct == b.Ct && a.Ut1 == b.Ut1 &&
+         a.Ut2 == b.Ut2 && a.Ut3 == b.Ut3;
 }
 
 PrefillWs carve_prefill(const tucker_attn_ctx* c, void* ws, int B, int N) {
@@ -259,8 +283,10 @@ int forward_core(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* X
   const void* ut2;
   long ut2_ld;
   PrepArgs pa = make_prep(c, w, ws.Gt, ws.Gtil2, ws.Wcat, ws.Ut2p, &ut2, &ut2_ld);
-  if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("prep_weights");
+  if (!c->prepared) {
+    if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("prep_weights");
+  }
 
   GemmArgs g;
   std::memset(&g, 0, sizeof(g));
@@ -393,7 +419,9 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
   if (f.use_rope && (long)pos0 + N > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
   if ((long)B * pad64(N) > (1l << 30) / 64 || B > 65535) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
+  if (c->prepared && !same_weights(*w, c->prepared_from)) return TUCKER_ATTN_INVALID_ARG;
   PrefillWs ws = carve_prefill(c, workspace, B, N);
+  use_prepared(c, ws);
   void *Vr = nullptr, *Krt = nullptr;
   float* lse = nullptr;
   size_t need = ws.bytes;
@@ -447,7 +475,9 @@ int tucker_attn_backward(tucker_attn_ctx* c, const tucker_attn_weights* w, const
   if (f.use_rope && (long)pos0 + N > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
   if ((long)B * pad64(N) > (1l << 21) || B > 65535) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
+  if (c->prepared && !same_weights(*w, c->prepared_from)) return TUCKER_ATTN_INVALID_ARG;
   BackwardWs ws = carve_backward(c, workspace, B, N);
+  use_prepared(c, ws.f);
   if (workspace_bytes < ws.bytes) return TUCKER_ATTN_WORKSPACE_TOO_SMALL;
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -616,7 +646,9 @@ int tucker_attn_decode(tucker_attn_ctx* c, const tucker_attn_weights* w, const v
   if (f.n_heads > 64) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
   if ((f.r3 * c->es) % 16 != 0 || (f.rt3 * c->es) % 16 != 0) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
+  if (c->prepared && !same_weights(*w, c->prepared_from)) return TUCKER_ATTN_INVALID_ARG;
   DecodeWs ws = carve_decode(c, workspace, B);
+  use_prepared(c, ws);
   if (workspace_bytes < ws.bytes) return TUCKER_ATTN_WORKSPACE_TOO_SMALL;
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -626,8 +658,10 @@ int tucker_attn_decode(tucker_attn_ctx* c, const tucker_attn_weights* w, const v
   const void* ut2;
   long ut2_ld;
   PrepArgs pa = make_prep(c, w, ws.Gt, ws.Gtil2, ws.Wcat, ws.Ut2p, &ut2, &ut2_ld);
-  if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("prep_weights");
+  if (!c->prepared) {
+    if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("prep_weights");
+  }
 
   GemmArgs g;
   std::memset(&g, 0, sizeof(g));
@@ -675,6 +709,32 @@ int tucker_attn_decode(tucker_attn_ctx* c, const tucker_attn_weights* w, const v
   yy.epi = 2; yy.Out = y; yy.ldo = f.d_model; yy.ksplit = 1;
   if (launch_gemm(f.dtype, yy, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
   rec.after("output_projection");
+  return TUCKER_ATTN_OK;
+}
+
+size_t tucker_attn_prepared_weights_bytes(const tucker_attn_ctx* c) { return c ? prepared_bytes(c) : 0; }
+
+int tucker_attn_prepare_weights(tucker_attn_ctx* c, const tucker_attn_weights* w, void* prepared, size_t bytes,
+                                void* hip_stream) {
+  if (!c || !weights_ok(c, w) || !prepared) return TUCKER_ATTN_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(prepared) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
+  if (bytes < prepared_bytes(c)) return TUCKER_ATTN_WORKSPACE_TOO_SMALL;
+  Carver cv{static_cast<char*>(prepared), 0};
+  void *Gt, *Gtil2, *Wcat, *Ut2p;
+  carve_weights(c, cv, Gt, Gtil2, Wcat, Ut2p);
+  const void* ut2;
+  long ut2_ld;
+  PrepArgs pa = make_prep(c, w, Gt, Gtil2, Wcat, Ut2p, &ut2, &ut2_ld);
+  if (launch_prep(c->cfg.dtype, pa, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  c->prepared = prepared;
+  c->prepared_from = *w;
+  return TUCKER_ATTN_OK;
+}
+
+int tucker_attn_release_weights(tucker_attn_ctx* c) {
+  if (!c) return TUCKER_ATTN_INVALID_ARG;
+  c->prepared = nullptr;
+  std::memset(&c->prepared_from, 0, sizeof(c->prepared_from));
   return TUCKER_ATTN_OK;
 }
 

@@ -55,6 +55,12 @@ class Layer:
     def __exit__(self, *exc):
         self.close()
 
+    def freeze_weights(self) -> None:
+        """Prepare the operand-layout copies of the weights once; later calls skip that step."""
+        self._prepared = torch.empty(max(ta.tucker_attn_prepared_weights_bytes(self.ctx), 256), dtype=torch.uint8,
+                                     device="cuda")
+        ta.tucker_attn_prepare_weights(self.ctx, self.weights, self._prepared)
+
     def workspace(self, nbytes: int) -> torch.Tensor:
         if self._ws is None or self._ws.numel() < nbytes:
             self._ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")

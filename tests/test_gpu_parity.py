@@ -444,3 +444,47 @@ def test_gpu_side_argument_errors():
         assert ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, 0, None, None, ws[:512], check=False) == -3
         assert ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, 0, None, None, ws, check=True) == 0
         torch.cuda.synchronize()
+
+
+# ---- prepared (frozen) weights -----------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prepared_weights_give_the_same_results_and_skip_the_preparation_kernel(dtype):
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=150, dtype=dtype, seed=61)
+    inp = wl.make_inputs(w)
+    with Layer(w, inp, max_positions=w.N + 8) as layer:
+        X = to_device(inp["X"], w.dtype)
+        y0 = layer.forward(X).clone()
+        ta.tucker_attn_profile_enable(layer.ctx, True)
+        layer.forward(X)
+        plain = [n for n, _ in ta.tucker_attn_profile_read(layer.ctx)]
+        layer.freeze_weights()
+        y1 = layer.forward(X).clone()
+        frozen = [n for n, _ in ta.tucker_attn_profile_read(layer.ctx)]
+        ta.tucker_attn_profile_enable(layer.ctx, False)
+        torch.cuda.synchronize()
+        assert "prep_weights" in plain and "prep_weights" not in frozen
+        assert torch.equal(y0, y1)
+        # other weight pointers than the prepared ones are refused; after release they are accepted again
+        other = dict(layer.weights, U2=layer.weights["U2"].clone())
+        ws = layer.workspace(ta.tucker_attn_workspace_bytes(layer.ctx, w.B, w.N))
+        assert ta.tucker_attn_forward(layer.ctx, other, X, torch.empty_like(X), 0, None, None, ws, check=False) == -1
+        ta.tucker_attn_release_weights(layer.ctx)
+        assert ta.tucker_attn_forward(layer.ctx, other, X, torch.empty_like(X), 0, None, None, ws, check=False) == 0
+        torch.cuda.synchronize()
+    check(to_host(y1), oracle_forward(w, inp), dtype, "frozen weights")
+
+
+def test_prepared_weights_in_decode():
+    w = wl.scaled(wl.WORKLOADS["decode_32k"], B=3, kv_len=300, d_model=256, n_heads=6, d_head=32, r1=2, r2=32, r3=64,
+                  recipe="fan_in", seed=62)
+    inp = wl.make_inputs(w)
+    with Layer(w, inp) as layer:
+        x = to_device(inp["X"][:, 0], w.dtype)
+        Kc0, Vc0 = to_device(inp["Kcache"], w.dtype), to_device(inp["Vcache"], w.dtype)
+        Kc1, Vc1 = Kc0.clone(), Vc0.clone()
+        y0 = layer.decode(x, Kc0, Vc0, inp["kv_len"]).clone()
+        layer.freeze_weights()
+        y1 = layer.decode(x, Kc1, Vc1, inp["kv_len"]).clone()
+        torch.cuda.synchronize()
+        assert torch.equal(y0, y1) and torch.equal(Kc0, Kc1) and torch.equal(Vc0, Vc1)
