@@ -115,8 +115,9 @@ struct BwdArgs {
   float* delta;        // [B][nH][Npad]  sum_c dO O
   void* Qr;            // [TP][nH][D] rotated, scaled per-head queries (acc order in c)
   void* dO;            // [TP][nH][D] (acc order in c)
-  void* dQ;            // [TP][nH][D] gradient of the unrotated per-head query / sqrt-free scale, acc order in c
-  float* dKp;          // [n_hg][TP][D] per-head-group partial gradients of the rotated keys / values
+  void* dQ;            // [TP][nH][D] dS K with the rotation removed (the 1/sqrt(d_head) is applied later), acc order in c
+  float* dKp;          // [n_hg][TP][D] per-head-group partial gradients of the rotated keys / values, channels at
+                       // their stored (acc-order) positions
   float* dVp;
   const float4* rope;
   int rope_ld;
