@@ -171,7 +171,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs p) {
       dof[cb] = to_frag<T>(da[cb]);
       const Frag<T> of = load_frag<T>(Orow + cb * 32);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) dsum += da[cb][e] * frag_elem(of, e);
+      for (int e = 0; e < 16; ++e) dsum += frag_elem(dof[cb], e) * frag_elem(of, e);   // the rounded dO that forms dP
     }
     const float delta = halves_sum(dsum);
     const float lse = p.lse[((long)b * p.nH + head) * p.Npad + m];    // +inf for padding tokens

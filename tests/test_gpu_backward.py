@@ -162,3 +162,41 @@ def test_backward_llama_full_size():
     # the LLaMA-7B-shaped workload at the size and launch configuration bench.py times (B=2, N=4096):
     # every gradient against the oracle (about a minute of fp64 work on the host)
     run_case(wl.WORKLOADS["llama7b_n4096"])
+
+
+def test_backward_vit_shape_many_sequences():
+    # enough sequences that the key/value gradient kernel gives several heads to one workgroup
+    run_case(wl.scaled(wl.WORKLOADS["vit_b"], B=64))
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_backward_random_small_configurations(seed):
+    rng = np.random.default_rng(5000 + seed)
+    dtype = ["f32", "bf16"][seed % 2]
+    shared = bool(rng.integers(0, 2))
+    r3 = int(rng.choice([8, 16, 24, 40, 48, 64, 72, 96, 128]))
+    rt3 = r3 if shared else int(rng.choice([8, 16, 32, 56, 64, 104, 128]))
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=int(rng.integers(1, 5)), N=int(rng.integers(1, 300)),
+                  d_model=int(rng.choice([64, 96, 200])), n_heads=int(rng.integers(1, 11)),
+                  d_head=int(rng.choice([16, 32, 64])), r1=int(rng.integers(2, 5)), r2=int(rng.choice([8, 32, 48, 80])),
+                  r3=r3, rt1=int(rng.integers(2, 5)), rt2=int(rng.choice([8, 32, 64, 100])), rt3=rt3, dtype=dtype,
+                  causal=bool(rng.integers(0, 2)), rope_base=[None, 1e4, 5e5][int(rng.integers(0, 3))],
+                  seed=6000 + seed, shared_kv=shared, pos0=int(rng.integers(0, 50)))
+    run_case(w, seed=7000 + seed)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_head_rank_one(dtype):
+    # r1 = 1: every head uses the same core slice, scaled by U1[i, 0].  dU1[i] = <dG_i, C[0]> is then a
+    # temperature-like gradient, sum over (query, key) of dS * S up to a factor, in which the row sums of dS
+    # cancel: with bf16 storage its few entries carry the rounding noise of the whole sum.  fp32 storage
+    # meets the common bar; for bf16 the head-factor gradients alone get 6e-2, all others the common bar.
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=140, d_model=96, n_heads=6, d_head=16, r1=1, r2=80, r3=48,
+                  rt1=1, rt2=8, rt3=128, dtype=dtype, rope_base=None, seed=6011)
+    inp = wl.make_inputs(w)
+    dY = upstream(w, 7011)
+    got, ref = run_backward(w, inp, dY), oracle_backward(w, inp, dY)
+    for k in ref:
+        bar = 6e-2 if (dtype == "bf16" and k in ("dU1", "dUt1")) else TOL[dtype]
+        err = orc.relative_l2(got[k], ref[k])
+        assert err <= bar, (k, err)
