@@ -1,8 +1,8 @@
 // Fused prefill attention for Tucker attention (Sections "Rotary Position Embedding" and
 // "Flash Attention" of the paper): per-head query Qhat_i = Qlat G_i built in a prologue,
 // latent RoPE applied to it in fp32 registers, then online-softmax attention over the ONE
-// latent K/V pair that all heads share, K/V tiles staged once in LDS per workgroup and
-// reused by every head in it.
+// latent K/V pair that all heads share, K/V tiles staged once in LDS per workgroup (loaded
+// from global memory straight into LDS, no register stage) and reused by every head in it.
 //
 // Everything is computed transposed so that an accumulator lane owns one query:
 //   Qhat^T[c][m] = sum_b Gt_i[c][b] Qlat[m][b]         rows c, columns m (queries)
@@ -23,8 +23,8 @@
 namespace ta {
 
 template <typename T, int D, int BC> struct AttnLds {
-  static constexpr int kKRowElems = D + 16 / sizeof(T);        // K tile rows: D channels + 16 B pad
-  static constexpr int kVRowElems = BC + 16 / sizeof(T);       // V^T tile rows: BC keys + 16 B pad
+  static constexpr int kKRowElems = D;                         // K tile rows: D channels, chunks swizzled
+  static constexpr int kVRowElems = BC;                        // V^T tile rows: BC keys, chunks swizzled
   static constexpr int kKElems = BC * kKRowElems;
   static constexpr int kVElems = D * kVRowElems;
   static constexpr int kStageElems = kKElems + kVElems;
@@ -58,44 +58,59 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
 
   // cooperative staging: K tile = BC rows x D, V^T tile = D rows x BC
   constexpr int KCH = BC * D / CE, VCH = D * BC / CE;           // 16-byte chunks
-  constexpr int KPT = (KCH + NT - 1) / NT, VPT = (VCH + NT - 1) / NT;
-  constexpr bool KFULL = KCH % NT == 0, VFULL = VCH % NT == 0;  // else the last round is partial
   constexpr int KCPR = D / CE, VCPR = BC / CE;                  // chunks per row
   const T* Kg = static_cast<const T*>(p.Kr) + tok_base * D;
   const T* Vg = static_cast<const T*>(p.Vt) + (long)b * D * p.Npad;
-  u32x4 kreg[KPT], vreg[VPT];
-  auto g_load = [&](int ktile, int vtile) {                    // K rows of ktile, V^T columns of vtile
-#pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-      int ci = threadIdx.x + i * NT;
-      int row = ci / KCPR, cc = ci % KCPR;
-      if (KFULL || ci < KCH) kreg[i] = *reinterpret_cast<const u32x4*>(Kg + (long)(ktile * BC + row) * D + cc * CE);
-    }
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      int ci = threadIdx.x + i * NT;
-      int row = ci / VCPR, cc = ci % VCPR;
-      if (VFULL || ci < VCH) vreg[i] = *reinterpret_cast<const u32x4*>(Vg + (long)row * p.Npad + vtile * BC + cc * CE);
-    }
-  };
-  auto s_store = [&](int stage) {
+  // Tiles go from global memory straight into LDS (no registers): one instruction of a wave fills
+  // 1 KB = 64 consecutive 16-byte chunks of the tile, lane l supplying the global address of the
+  // chunk that belongs at position l.  Rows are not padded; instead chunk c of row r sits at
+  // position c ^ ((r / W) & mask) of its row, which spreads the 16 rows that one fragment read
+  // touches over all banks.
+  constexpr int NWV = NT / 64;
+  constexpr int WK = KCPR >= 16 ? 1 : 16 / KCPR, MK = (KCPR >= 16 ? 16 : KCPR) - 1;
+  constexpr int WV = VCPR >= 16 ? 1 : 16 / VCPR, MV = (VCPR >= 16 ? 16 : VCPR) - 1;
+  static_assert(KCH % 64 == 0 && VCH % 64 == 0, "whole 1 KB pieces");
+  auto dma_load = [&](int ktile, int vtile, int stage) {
     T* ks = smem + (long)stage * L::kStageElems;
     T* vs = ks + L::kKElems;
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-      int ci = threadIdx.x + i * NT;
-      int row = ci / KCPR, cc = ci % KCPR;
-      if (KFULL || ci < KCH) *reinterpret_cast<u32x4*>(ks + row * L::kKRowElems + cc * CE) = kreg[i];
+    for (int i = 0; i < (KCH / 64 + NWV - 1) / NWV; ++i) {
+      const int q = i * NWV + wave;                              // 1 KB piece of the K tile
+      if (q < KCH / 64) {
+        const int ci = q * 64 + lane, row = ci / KCPR, pos = ci % KCPR;
+        const int c = pos ^ ((row / WK) & MK);
+        const T* g = Kg + (long)(ktile * BC + row) * D + c * CE;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                         (__attribute__((address_space(3))) void*)(ks + q * 64 * CE), 16, 0, 0);
+      }
     }
 #pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      int ci = threadIdx.x + i * NT;
-      int row = ci / VCPR, cc = ci % VCPR;
-      if (VFULL || ci < VCH) *reinterpret_cast<u32x4*>(vs + row * L::kVRowElems + cc * CE) = vreg[i];
+    for (int i = 0; i < (VCH / 64 + NWV - 1) / NWV; ++i) {
+      const int q = i * NWV + wave;
+      if (q < VCH / 64) {
+        const int ci = q * 64 + lane, row = ci / VCPR, pos = ci % VCPR;
+        const int c = pos ^ ((row / WV) & MV);
+        const T* g = Vg + (long)row * p.Npad + vtile * BC + c * CE;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                         (__attribute__((address_space(3))) void*)(vs + q * 64 * CE), 16, 0, 0);
+      }
     }
   };
+  const int xk = (lr / WK) & MK, xv = (lr / WV) & MV;            // swizzle of this lane's fragment rows
+  // fragment of row-chunks k0 .. (16 elements) of a swizzled row
+  auto frag_swz = [&](const T* rowp, int k0, int x) -> Frag<T> {
+    Frag<T> f;
+    if constexpr (sizeof(T) == 2) {
+      f.v[0] = *reinterpret_cast<const bf16x8*>(rowp + ((k0) ^ x) * CE);
+      f.v[1] = *reinterpret_cast<const bf16x8*>(rowp + ((k0 + 1) ^ x) * CE);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) f.v[j] = *reinterpret_cast<const f32x4*>(rowp + ((k0 + j) ^ x) * CE);
+    }
+    return f;
+  };
 
-  g_load(0, 0);                                                // in flight during the prologue
+  dma_load(0, 0, 0);                                           // in flight during the prologue (the V part of stage 0 is never read)
 
   // ---- prologue: Qhat^T = Gt_i * Qlat^T, RoPE, -> B-operand fragments ---------------------
   // Operand fragments are fetched two contraction blocks ahead of their product; the rotation
@@ -226,12 +241,13 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
     constexpr bool PV = decltype(pv_c)::value, SS = decltype(ss_c)::value;
     constexpr int NPV = PV ? CB * NB : 0, NSS = SS ? NB * CB : 0, TOT = NPV + NSS;
     const T* st = smem + (long)(tile & 1) * L::kStageElems;    // K(tile) and V(tile-1) share a stage
-    const T* kbase = st + lr * L::kKRowElems + 16 * h;
-    const T* vbase = st + L::kKElems + lr * L::kVRowElems + 16 * h;
+    const T* kbase = st + lr * L::kKRowElems;
+    const T* vbase = st + L::kKElems + lr * L::kVRowElems;
+    constexpr int FC = 16 / CE;                                   // 16-byte chunks per fragment half-slice
     auto fetch = [&](int i) -> Frag<T> {
-      if (i < NPV) return load_frag<T>(vbase + (i / NB) * 32 * L::kVRowElems + (i % NB) * 32);
+      if (i < NPV) return frag_swz(vbase + (i / NB) * 32 * L::kVRowElems, (i % NB) * 2 * FC + h * FC, xv);
       const int j = i - NPV;
-      return load_frag<T>(kbase + (j / CB) * 32 * L::kKRowElems + (j % CB) * 32);
+      return frag_swz(kbase + (j / CB) * 32 * L::kKRowElems, (j % CB) * 2 * FC + h * FC, xk);
     };
     Frag<T> ring[kRing];
 #pragma unroll
@@ -312,33 +328,35 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
     }
   };
 
-  s_store(0);                                                   // K(0); the V part of stage 0 is never read
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   const int last = n_tiles - 1;
+  // interval t reads stage t&1 = {K(t), V(t-1)}; stage (t+1)&1 was last read in interval t-1, so the
+  // pair of interval t+1 is fetched into it while interval t computes
   if (wave < NT / 128) {                                        // ---- MFMA phase first
-    g_load(min(1, last), 0);
+    dma_load(min(1, last), 0, 1);
     mfma_phase(kNo, kYes, 0);
     do_softmax(0);
-    s_store(1);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     for (int t = 1; t < n_tiles; ++t) {
-      g_load(min(t + 1, last), t);
+      dma_load(min(t + 1, last), t, (t + 1) & 1);
       mfma_phase(kYes, kYes, t);
       do_softmax(t);
-      s_store((t + 1) & 1);
+      __builtin_amdgcn_s_waitcnt(0);
       __syncthreads();
     }
     mfma_phase(kYes, kNo, n_tiles);
   } else {                                                      // ---- softmax phase first
-    g_load(min(1, last), 0);
+    dma_load(min(1, last), 0, 1);
     mfma_phase(kNo, kYes, 0);
-    s_store(1);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     for (int t = 1; t < n_tiles; ++t) {
-      g_load(min(t + 1, last), t);
+      dma_load(min(t + 1, last), t, (t + 1) & 1);
       do_softmax(t - 1);
       mfma_phase(kYes, kYes, t);
-      s_store((t + 1) & 1);
+      __builtin_amdgcn_s_waitcnt(0);
       __syncthreads();
     }
     do_softmax(last);
