@@ -246,7 +246,7 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs p) {
 // ---- dK, dV ------------------------------------------------------------------------------------------
 template <typename T, int D, int TQ> struct DkvLds {
   static constexpr int kStages = 3;
-  static constexpr int kRow = D + 16 / sizeof(T);               // Q / dO rows, padded by 16 bytes
+  static constexpr int kRow = D;                                // Q / dO rows, unpadded, chunks swizzled
   static constexpr int kRElems = TQ * kRow;
   static constexpr int kStageElems = 2 * kRElems;
   static constexpr size_t kStageBytes = kStageElems * sizeof(T) + 2ul * TQ * sizeof(float);
@@ -260,7 +260,8 @@ template <typename T, int D, int TQ> struct DkvLds {
 // pair, leaves them in LDS and accumulates dV^T += dO^T P; wave w+4 holds the values, forms dP one
 // interval later, takes P from LDS, and accumulates dK^T += Q^T (P (dP - delta)).  Two resident
 // waves per SIMD let one wave's exponentials overlap the other's matrix products.  The Q and dO rows
-// of a pair are staged once, row-major; the transposed operands Q^T and dO^T are read from the same
+// of a pair are staged once, row-major (straight from global memory into LDS, three stages, two pairs
+// ahead); the transposed operands Q^T and dO^T are read from the same
 // tiles with transposing LDS loads, so their rows (the channels) come out in the stored channel
 // order of Q and dO (acc order within 32-blocks), which kv_reduce undoes.
 template <typename T, int D, int TQ>
@@ -310,57 +311,50 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
   // (with causal masking their ranges start at different blocks but all end at the last).
   auto q_of = [&](int it) { return (qb_first + n_qb - 1 - it % n_qb) * TQ; };
 
-  // A staged pair travels global -> registers -> LDS.  PF pairs are in flight in registers, so a
-  // round trip to memory is hidden behind PF-1 intervals of work (one interval is shorter than the
-  // memory latency).  No load sits behind a branch.
-  constexpr int RCH = TQ * D / CE, PT = (RCH + NT - 1) / NT;    // chunks per tensor, per thread
-  constexpr bool FULL = RCH % NT == 0;
-  constexpr int RCPR = D / CE;
-  constexpr int PF = 3;
-  struct Slot { u32x4 q[PT], o[PT]; float stat; } sl[PF];
-  auto g_load = [&](Slot& r, int it_raw) {
+  // The Q and dO rows of a pair go from global memory straight into LDS (see dma_piece in common.h),
+  // into the stage that the lagging dK^T waves have just left, one interval before the dV^T waves
+  // need them; only the two small per-query vectors pass through a register.  That register load is
+  // issued last and waited for before it is stored, and loads return in order, so the tiles of a
+  // pair have landed when its vectors are stored (and the barrier that follows publishes both).
+  constexpr int CPR = D / CE;                                    // chunks per row
+  constexpr int PIECES = TQ * CPR / 64;                          // 1 KB pieces per tensor
+  constexpr int PF = 2;                                         // pairs in flight
+  float stat[PF];
+  auto g_load = [&](float& st_reg, int it_raw, int stage) {
     const int it = min(it_raw, n_it - 1);                       // past the end: the last pair again, never read
     const int head = head0 + it / n_qb, q0 = q_of(it);
     const T* Qg = static_cast<const T*>(p.Qr) + ((tok_base + q0) * p.nH + head) * D;
     const T* Og = static_cast<const T*>(p.dO) + ((tok_base + q0) * p.nH + head) * D;
+    T* qs = reinterpret_cast<T*>(smem_raw + (size_t)stage * L::kStageBytes);
+    T* os = qs + L::kRElems;
+    const long rs = (long)p.nH * D;
 #pragma unroll
-    for (int i = 0; i < PT; ++i) {
-      const int ci = FULL ? threadIdx.x + i * NT : min((int)threadIdx.x + i * NT, RCH - 1);
-      const int row = ci / RCPR, cc = ci % RCPR;
-      r.q[i] = *reinterpret_cast<const u32x4*>(Qg + (long)row * p.nH * D + cc * CE);
-      r.o[i] = *reinterpret_cast<const u32x4*>(Og + (long)row * p.nH * D + cc * CE);
+    for (int i = 0; i < (PIECES + 7) / 8; ++i) {
+      const int q = i * 8 + wave;
+      if (q < PIECES) {
+        dma_piece<T, CPR>(qs, q, lane, [&](int row) { return Qg + row * rs; });
+        dma_piece<T, CPR>(os, q, lane, [&](int row) { return Og + row * rs; });
+      }
     }
     // threads 0..255 fetch the log-sum-exp of the block's queries, threads 256.. their delta (TQ of
     // each are kept)
     const long so = ((long)b * p.nH + head) * p.Npad + q0 + threadIdx.x % TQ;
-    r.stat = (threadIdx.x < 256 ? p.lse : p.delta)[so];
+    st_reg = (threadIdx.x < 256 ? p.lse : p.delta)[so];
   };
-  auto s_store = [&](const Slot& r, int stage) {
-    unsigned char* sb = smem_raw + (size_t)stage * L::kStageBytes;
-    T* qs = reinterpret_cast<T*>(sb);
-    T* os = qs + L::kRElems;
-    float* stat = reinterpret_cast<float*>(os + L::kRElems);
-#pragma unroll
-    for (int i = 0; i < PT; ++i) {
-      const int ci = threadIdx.x + i * NT;
-      if (!FULL && ci >= RCH) break;
-      const int row = ci / RCPR, cc = ci % RCPR;
-      *reinterpret_cast<u32x4*>(qs + row * L::kRow + cc * CE) = r.q[i];
-      *reinterpret_cast<u32x4*>(os + row * L::kRow + cc * CE) = r.o[i];
-    }
+  auto s_store = [&](float st_reg, int stage) {
+    float* st = reinterpret_cast<float*>(smem_raw + (size_t)stage * L::kStageBytes + L::kStageElems * sizeof(T));
     // stored negated: a score block starts from -log-sum-exp, a dP block from -delta
-    if (threadIdx.x < TQ) stat[threadIdx.x] = -r.stat;
-    else if (threadIdx.x >= 256 && threadIdx.x < 256 + TQ) stat[TQ + threadIdx.x - 256] = -r.stat;
+    if (threadIdx.x < TQ) st[threadIdx.x] = -st_reg;
+    else if (threadIdx.x >= 256 && threadIdx.x < 256 + TQ) st[TQ + threadIdx.x - 256] = -st_reg;
   };
 
-#pragma unroll
-  for (int u = 0; u < PF; ++u) g_load(sl[u], u);
-  s_store(sl[0], 0);
-  g_load(sl[0], PF);
+  g_load(stat[0], 0, 0);
+  g_load(stat[1], 1, 1);
+  s_store(stat[0], 0);
   __syncthreads();
-  // one interval: work on the staged pair, then move pair t+1 from its register slot to its LDS
-  // stage and refill that slot at once with the pair PF further on.  The dK^T waves run one pair
-  // behind the dV^T waves (three stages are live).
+  // one interval: the dV^T waves work on pair t (stage t % 3), the dK^T waves on pair t-1; then the
+  // vectors of pair t+1 are stored, and after the barrier pair t+2 is fetched into stage (t+2) % 3,
+  // which held pair t-1.
   auto interval = [&](auto slot_c, int t) {
     constexpr int S1 = (decltype(slot_c)::value + 1) % PF;      // slot of pair t + 1
     const int it = k_role ? t - 1 : t;                          // pair this wave works on in this interval
@@ -385,9 +379,11 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) a[4 * q + e] = v4[e];
         }
-        const T* rows = (k_role ? os : qs) + (qb * 32 + lr) * L::kRow + 16 * h;
+        const T* rows = (k_role ? os : qs) + (qb * 32 + lr) * L::kRow;
+        constexpr int FC = 16 / CE;                             // chunks per fragment half
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) mma32(a, load_frag<T>(rows + cb * 32), kop[cb]);
+        for (int cb = 0; cb < CB; ++cb)
+          mma32(a, load_frag_swz<T>(rows, cb * 2 * FC + h * FC, swz_x<CPR>(qb * 32 + lr)), kop[cb]);
         Frag<T> bf;                                             // P (dV^T wave) or dS (dK^T wave), k = queries
         if (!k_role) {
           if (key0 + 31 >= p.N || (p.causal && key0 + 31 > qfirst)) {   // a key past the sequence or after a query
@@ -409,22 +405,20 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(BwdArgs p) {
         }
         const T* tile = k_role ? qs : os;                       // dK^T += Q^T dS,  dV^T += dO^T P
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) mma32(acc[cb], load_frag_tr(tile, L::kRow, qb * 32, cb * 32, lane), bf);
+        for (int cb = 0; cb < CB; ++cb) mma32(acc[cb], load_frag_tr_swz<CPR>(tile, qb * 32, cb * 32, lane), bf);
       }
     }
-    s_store(sl[S1], (t + 1) % NS);
-    g_load(sl[S1], t + 1 + PF);
+    s_store(stat[S1], (t + 1) % NS);
     __syncthreads();
+    if (t + 2 < n_it) g_load(stat[decltype(slot_c)::value], t + 2, (t + 2) % NS);   // nothing is left in flight at the end
   };
   const int n_int = n_it + 1;
   int t = 0;
   for (; t + PF <= n_int; t += PF) {
     interval(std::integral_constant<int, 0>{}, t);
     interval(std::integral_constant<int, 1>{}, t + 1);
-    interval(std::integral_constant<int, 2>{}, t + 2);
   }
   if (t < n_int) interval(std::integral_constant<int, 0>{}, t);
-  if (t + 1 < n_int) interval(std::integral_constant<int, 1>{}, t + 1);
 
   // rows of the accumulators are stored channel positions: position 16h'+4q'+r of a 32-block
   if (key_ok) {

@@ -206,6 +206,71 @@ __device__ __forceinline__ Frag<float> load_frag_tr(const float* tile, int strid
   return f;
 }
 
+// ---- unpadded LDS tiles with swizzled 16-byte chunks ---------------------------------------------
+// A tile row of CPR chunks is stored without padding; chunk c of row r sits at chunk position
+// c ^ swz_x<CPR>(r).  The 16 consecutive rows that one fragment read touches then fall into
+// different banks.  (This is the layout that direct global-to-LDS loads can produce: one such load
+// of a wave fills 64 consecutive chunks, lane l choosing which global chunk lands at position l.)
+template <int CPR> __host__ __device__ constexpr int swz_x(int row) {
+  constexpr int W = CPR >= 16 ? 1 : 16 / CPR, M = (CPR >= 16 ? 16 : CPR) - 1;
+  return (row / W) & M;
+}
+// 16 consecutive elements, starting at chunk k0, of a swizzled row (x = swz_x of that row)
+template <typename T> __device__ __forceinline__ Frag<T> load_frag_swz(const T* rowp, int k0, int x);
+template <> __device__ __forceinline__ Frag<bf16> load_frag_swz<bf16>(const bf16* rowp, int k0, int x) {
+  Frag<bf16> f;
+  f.v[0] = *reinterpret_cast<const bf16x8*>(rowp + ((k0) ^ x) * 8);
+  f.v[1] = *reinterpret_cast<const bf16x8*>(rowp + ((k0 + 1) ^ x) * 8);
+  return f;
+}
+template <> __device__ __forceinline__ Frag<float> load_frag_swz<float>(const float* rowp, int k0, int x) {
+  Frag<float> f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) f.v[j] = *reinterpret_cast<const f32x4*>(rowp + ((k0 + j) ^ x) * 4);
+  return f;
+}
+// load_frag_tr on a swizzled tile whose rows hold CPR chunks (stride = CPR * elements per chunk)
+template <int CPR>
+__device__ __forceinline__ Frag<bf16> load_frag_tr_swz(const bf16* tile, int row0, int col0, int lane) {
+  const int h = lane / 32, i = lane % 16;
+  const int col = col0 + (lane & 16) + 4 * (i % 4);              // 4 consecutive columns: half a chunk
+  Frag<bf16> f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = row0 + 8 * q + 4 * h + i / 4;
+    const bf16* src = tile + row * (CPR * 8) + (((col / 8) ^ swz_x<CPR>(row)) * 8) + col % 8;
+    auto* lp = (__attribute__((address_space(3))) s16x4*)(src);
+    const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(lp);
+    const bf16x4 b = __builtin_bit_cast(bf16x4, v);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) f.v[q / 2][(q % 2) * 4 + r] = b[r];
+  }
+  return f;
+}
+template <int CPR>
+__device__ __forceinline__ Frag<float> load_frag_tr_swz(const float* tile, int row0, int col0, int lane) {
+  const int h = lane / 32, col = col0 + lane % 32;
+  Frag<float> f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = row0 + 8 * q + 4 * h + r;
+      f.v[q][r] = tile[row * (CPR * 4) + (((col / 4) ^ swz_x<CPR>(row)) * 4) + col % 4];
+    }
+  return f;
+}
+// one direct global-to-LDS load of this wave: 64 consecutive chunks of a swizzled tile starting at
+// chunk q*64; `row_ptr(row)` gives the global address of tile row `row`
+template <typename T, int CPR, class RowPtr>
+__device__ __forceinline__ void dma_piece(T* tile, int q, int lane, RowPtr row_ptr) {
+  constexpr int CE = 16 / (int)sizeof(T);
+  const int ci = q * 64 + lane, row = ci / CPR, pos = ci % CPR;
+  const T* g = row_ptr(row) + (pos ^ swz_x<CPR>(row)) * CE;
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                   (__attribute__((address_space(3))) void*)(tile + q * 64 * CE), 16, 0, 0);
+}
+
 // four consecutive accumulator registers (rows 8q+4h .. +3) -> 4 elements of T at p (natural order)
 __device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
   *reinterpret_cast<f32x4*>(p) = f32x4{a, b, c, d};
