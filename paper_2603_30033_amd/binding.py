@@ -23,6 +23,10 @@ EXPORTED = [
     "tucker_attn_prepared_weights_bytes", "tucker_attn_prepare_weights", "tucker_attn_release_weights",
     "tucker_attn_profile_enable", "tucker_attn_profile_read", "tucker_attn_status_string",
 ]
+EXPORTED_CONVERT = [
+    "tucker_convert_from_gqa", "tucker_convert_from_mla", "tucker_convert_hosvd_workspace_bytes",
+    "tucker_convert_from_mha_hosvd",
+]
 
 
 class TuckerAttnError(RuntimeError):
@@ -47,6 +51,13 @@ GRAD_KEYS = ("dC", "dU1", "dU2", "dU3", "dCt", "dUt1", "dUt2", "dUt3")
 
 class tucker_attn_grads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in GRAD_KEYS]
+
+
+WEIGHT_KEYS = ("C", "U1", "U2", "U3", "Ct", "Ut1", "Ut2", "Ut3")
+
+
+class tucker_convert_weights_out(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_KEYS]
 
 
 _lib = None
@@ -97,6 +108,16 @@ def load_library() -> C.CDLL:
     lib.tucker_attn_profile_read.restype = C.c_int
     lib.tucker_attn_status_string.argtypes = [C.c_int]
     lib.tucker_attn_status_string.restype = C.c_char_p
+    out_p = C.POINTER(tucker_convert_weights_out)
+    lib.tucker_convert_from_gqa.argtypes = [C.c_int32] * 5 + [C.c_void_p] * 4 + [out_p, C.c_void_p]
+    lib.tucker_convert_from_gqa.restype = C.c_int
+    lib.tucker_convert_from_mla.argtypes = [C.c_int32] * 6 + [C.c_void_p] * 7 + [out_p, C.c_void_p]
+    lib.tucker_convert_from_mla.restype = C.c_int
+    lib.tucker_convert_hosvd_workspace_bytes.argtypes = [C.c_int32] * 3
+    lib.tucker_convert_hosvd_workspace_bytes.restype = C.c_size_t
+    lib.tucker_convert_from_mha_hosvd.argtypes = [C.c_int32] * 4 + [C.c_void_p] * 4 + [C.c_int32] * 7 + [
+        out_p, C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.tucker_convert_from_mha_hosvd.restype = C.c_int
     _lib = lib
     return lib
 
@@ -235,3 +256,59 @@ def tucker_attn_profile_read(ctx: int) -> List[Tuple[str, float]]:
     if n < 0:
         _check(n, "tucker_attn_profile_read")
     return [(names[i].decode(), float(ms[i])) for i in range(n)]
+
+
+# ---- weight front-ends (include/tucker_convert.h) ------------------------------------------------
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return TUCKER_ATTN_F32
+    if t.dtype == torch.bfloat16:
+        return TUCKER_ATTN_BF16
+    raise TuckerAttnError(f"unsupported storage type {t.dtype}")
+
+
+def _out_struct(out: Dict) -> tucker_convert_weights_out:
+    return tucker_convert_weights_out(*[_ptr(out.get(k)) for k in WEIGHT_KEYS])
+
+
+def tucker_convert_from_gqa(WQ, WK, WV, WO, n_heads: int, n_groups: int, out: Dict, stream=None,
+                            check: bool = True) -> int:
+    """out: dict of preallocated device tensors C, U1, U2, U3, Ct, Ut1, Ut2, Ut3."""
+    d, n = WQ.shape
+    st = load_library().tucker_convert_from_gqa(_dtype_code(WQ), d, n_heads, n // n_heads, n_groups, _ptr(WQ), _ptr(WK),
+                                                _ptr(WV), _ptr(WO), C.byref(_out_struct(out)), _stream_ptr(stream))
+    if check:
+        _check(st, "tucker_convert_from_gqa")
+    return st
+
+
+def tucker_convert_from_mla(WDQ, WUQ, WDKV, WUK, WDV, WUV, WO, n_heads: int, out: Dict, stream=None,
+                            check: bool = True) -> int:
+    d, dcq = WDQ.shape
+    dck, n = WUK.shape
+    st = load_library().tucker_convert_from_mla(_dtype_code(WDQ), d, n_heads, n // n_heads, dcq, dck, _ptr(WDQ), _ptr(WUQ),
+                                                _ptr(WDKV), _ptr(WUK), _ptr(WDV), _ptr(WUV), _ptr(WO),
+                                                C.byref(_out_struct(out)), _stream_ptr(stream))
+    if check:
+        _check(st, "tucker_convert_from_mla")
+    return st
+
+
+def tucker_convert_hosvd_workspace_bytes(d: int, n_heads: int, d_head: int) -> int:
+    return int(load_library().tucker_convert_hosvd_workspace_bytes(d, n_heads, d_head))
+
+
+def tucker_convert_from_mha_hosvd(WQ, WK, WV, WO, n_heads: int, ranks, ranks_t, shared_kv: bool, out: Dict,
+                                  workspace, want_singular_values: bool = False, stream=None, check: bool = True):
+    """Returns (status, singular values as a list of 2*(nH+2d) floats or None)."""
+    d, n = WQ.shape
+    sv = (C.c_double * (2 * (n_heads + 2 * d)))() if want_singular_values else None
+    st = load_library().tucker_convert_from_mha_hosvd(
+        _dtype_code(WQ), d, n_heads, n // n_heads, _ptr(WQ), _ptr(WK), _ptr(WV), _ptr(WO), *[int(r) for r in ranks],
+        *[int(r) for r in ranks_t], int(bool(shared_kv)), C.byref(_out_struct(out)), sv, _ptr(workspace),
+        workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream_ptr(stream))
+    if check:
+        _check(st, "tucker_convert_from_mha_hosvd")
+    return st, (list(sv) if sv is not None else None)

@@ -30,8 +30,10 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 class Layer:
     """A context plus device copies of one workload's weights."""
 
-    def __init__(self, w: wl.Workload, inp: Dict[str, np.ndarray], max_positions: Optional[int] = None,
-                 save_for_backward: bool = False):
+    def __init__(self, w: wl.Workload, inp: Optional[Dict[str, np.ndarray]], max_positions: Optional[int] = None,
+                 save_for_backward: bool = False, device_weights: Optional[Dict[str, torch.Tensor]] = None):
+        """Weights come from the host arrays `inp`, or are the device tensors `device_weights` (e.g. what a
+        conversion entry point wrote)."""
         self.w = w
         rt1, rt2, rt3 = w.ranks_post()
         if max_positions is None:
@@ -41,7 +43,10 @@ class Layer:
             rt1=rt1, rt2=rt2, rt3=rt3, causal=w.causal, rope_base=w.rope_base, dtype=w.dtype,
             max_positions=max_positions, shared_kv=w.shared_kv, save_for_backward=save_for_backward)
         # with a shared key-value projection the library never reads the value basis: it gets none
-        self.weights = {k: to_device(inp[k], w.dtype) for k in W_KEYS if not (w.shared_kv and k == "Ut3")}
+        if device_weights is not None:
+            self.weights = {k: device_weights[k] for k in W_KEYS if not (w.shared_kv and k == "Ut3")}
+        else:
+            self.weights = {k: to_device(inp[k], w.dtype) for k in W_KEYS if not (w.shared_kv and k == "Ut3")}
         self._ws = None
 
     def close(self):
@@ -90,3 +95,48 @@ class Layer:
         ws = self.workspace(ta.tucker_attn_decode_workspace_bytes(self.ctx, x.shape[0]))
         ta.tucker_attn_decode(self.ctx, self.weights, x, y, Kc, Vc, [int(v) for v in kv_len], ws)
         return y
+
+
+# ---- weight front-ends ---------------------------------------------------------------------------
+
+def _empty_weights(shapes: Dict[str, tuple], like: torch.Tensor) -> Dict[str, torch.Tensor]:
+    return {k: torch.empty(shape, dtype=like.dtype, device="cuda") for k, shape in shapes.items()}
+
+
+def from_gqa(WQ, WK, WV, WO, n_heads: int, n_groups: int) -> Dict[str, torch.Tensor]:
+    """Device tensors of classic GQA weights -> device tensors of the equivalent Tucker weights."""
+    d, n = WQ.shape
+    g = WK.shape[1]
+    out = _empty_weights(dict(C=(n_heads, n, g), U1=(n_heads, n_heads), U2=(d, n), U3=(d, g), Ct=(n_heads, n, g),
+                              Ut1=(n_heads, n_heads), Ut2=(d, n), Ut3=(d, g)), WQ)
+    ta.tucker_convert_from_gqa(WQ, WK, WV, WO, n_heads, n_groups, out)
+    return out
+
+
+def from_mla(WDQ, WUQ, WDKV, WUK, WDV, WUV, WO, n_heads: int) -> Dict[str, torch.Tensor]:
+    d, dcq = WDQ.shape
+    dck, n = WUK.shape
+    shapes = dict(C=(n_heads, dcq, dck), U1=(n_heads, n_heads), U2=(d, dcq), U3=(d, dck), Ct=(n_heads, n, dck),
+                  Ut1=(n_heads, n_heads), Ut2=(d, n))
+    if WDV is not None:
+        shapes["Ut3"] = (d, dck)
+    out = _empty_weights(shapes, WDQ)
+    ta.tucker_convert_from_mla(WDQ, WUQ, WDKV, WUK, WDV, WUV, WO, n_heads, out)
+    return out
+
+
+def from_mha_hosvd(WQ, WK, WV, WO, n_heads: int, ranks, ranks_t, shared_kv: bool = False,
+                   want_singular_values: bool = False):
+    """Returns (device Tucker weights, singular values or None)."""
+    d, n = WQ.shape
+    (r1, r2, r3), (t1, t2, t3) = ranks, ranks_t
+    shapes = dict(C=(r1, r2, r3), U1=(n_heads, r1), U2=(d, r2), U3=(d, r3), Ct=(t1, t2, t3), Ut1=(n_heads, t1),
+                  Ut2=(d, t2))
+    if not shared_kv:
+        shapes["Ut3"] = (d, t3)
+    out = _empty_weights(shapes, WQ)
+    ws = torch.empty(max(ta.tucker_convert_hosvd_workspace_bytes(d, n_heads, n // n_heads), 256), dtype=torch.uint8,
+                     device="cuda")
+    _, sv = ta.tucker_convert_from_mha_hosvd(WQ, WK, WV, WO, n_heads, ranks, ranks_t, shared_kv, out, ws,
+                                             want_singular_values=want_singular_values)
+    return out, sv

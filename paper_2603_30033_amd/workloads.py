@@ -145,6 +145,26 @@ def _normal(rng, shape, std):
     return (rng.standard_normal(shape) * std).astype(np.float32)
 
 
+def make_classic_weights(d: int, n_heads: int, d_head: int, seed: int, dtype: str, kv_width: Optional[int] = None,
+                         decay: float = 0.5) -> Dict[str, np.ndarray]:
+    """Seeded stand-ins for trained MHA / GQA projection matrices: WQ [d, nH dH], WK, WV [d, kv_width]
+    (default nH dH), WO [nH dH, d].  Each is an orthonormal basis of the model dimension with a power-law
+    weighting j^-decay times a Gaussian mixing matrix, so that the mode unfoldings of the stacked per-head
+    products have decaying spectra (as trained layers do) instead of a flat one.  fp32 arrays already
+    rounded to the storage type."""
+    rng = np.random.default_rng(seed)
+    n = n_heads * d_head
+    g = n if kv_width is None else kv_width
+    s = np.power(1.0 + np.arange(d), -decay)
+
+    def one(cols):
+        basis = _orthonormal(rng, d, d).astype(np.float64)
+        return (basis * s) @ rng.standard_normal((d, cols)) / np.sqrt(np.sum(s * s))
+
+    out = dict(WQ=one(n), WK=one(g), WV=one(g), WO=one(n).T.copy())
+    return {k: round_to_storage(v.astype(np.float32), dtype) for k, v in out.items()}
+
+
 def make_inputs(w: Workload) -> Dict[str, np.ndarray]:
     """All tensors of one workload, fp32 arrays already rounded to the storage dtype.
 

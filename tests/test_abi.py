@@ -11,18 +11,45 @@ from paper_2603_30033_amd import binding as ta
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def header_functions():
-    text = open(os.path.join(ROOT, "include", "tucker_attn.h")).read()
+def header_functions(header="tucker_attn.h", prefix="tucker_attn_"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tucker_attn_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(" + prefix + r"[a-z_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
     lib = ta.load_library()
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["tucker_attn.h", "tucker_convert.h"]
     names = header_functions()
     assert sorted(ta.EXPORTED) == names
-    for n in names:
+    convert = header_functions("tucker_convert.h", "tucker_convert_")
+    assert sorted(ta.EXPORTED_CONVERT) == convert
+    for n in names + convert:
         assert getattr(lib, n) is not None
+
+
+def test_conversion_entry_points_reject_bad_arguments_on_the_host():
+    lib = ta.load_library()
+    out = ta.tucker_convert_weights_out(*([256] * 8))
+    o = C.byref(out)
+    assert lib.tucker_convert_from_gqa(0, 64, 4, 16, 3, 256, 256, 256, 256, o, None) == -1        # 3 does not divide 4
+    assert lib.tucker_convert_from_gqa(2, 64, 4, 16, 2, 256, 256, 256, 256, o, None) == -1        # unknown storage type
+    assert lib.tucker_convert_from_gqa(0, 64, 4, 16, 2, None, 256, 256, 256, o, None) == -1
+    assert lib.tucker_convert_from_mla(0, 64, 4, 16, 0, 8, 256, 256, 256, 256, None, 256, 256, o, None) == -1
+    no_ut3 = ta.tucker_convert_weights_out(*([256] * 7 + [None]))
+    assert lib.tucker_convert_from_mla(0, 64, 4, 16, 8, 8, 256, 256, 256, 256, 256, 256, 256, C.byref(no_ut3), None) == -1
+    assert ta.tucker_convert_hosvd_workspace_bytes(0, 4, 16) == 0
+    assert ta.tucker_convert_hosvd_workspace_bytes(16384, 4, 16) == 0
+    nbytes = ta.tucker_convert_hosvd_workspace_bytes(64, 4, 16)
+    assert nbytes > 0 and nbytes % 256 == 0
+    hosvd = lambda *a: lib.tucker_convert_from_mha_hosvd(*a)
+    W = [256] * 4
+    assert hosvd(0, 64, 4, 16, *W, 5, 8, 8, 4, 8, 8, 0, o, None, 256, 1 << 40, None) == -1         # r1 > nH
+    assert hosvd(0, 64, 4, 16, *W, 4, 65, 8, 4, 8, 8, 0, o, None, 256, 1 << 40, None) == -1        # r2 > d
+    assert hosvd(0, 64, 4, 16, *W, 4, 8, 8, 4, 8, 4, 1, o, None, 256, 1 << 40, None) == -1         # shared needs rt3 == r3
+    assert hosvd(0, 64, 4, 16, *W, 4, 8, 8, 4, 8, 8, 0, o, None, 256, 16, None) == -3              # workspace too small
+    assert hosvd(0, 64, 4, 16, *W, 4, 8, 8, 4, 8, 8, 0, o, None, 257, 1 << 40, None) == -1         # misaligned workspace
+    assert hosvd(0, 16384, 4, 16, *W, 4, 8, 8, 4, 8, 8, 0, o, None, 256, 1 << 40, None) == -2
 
 
 def test_status_strings():

@@ -1,0 +1,243 @@
+"""GPU parity of the weight front-ends (classic attention weights -> Tucker weights), called through
+the C ABI, against the conversion oracle on the same seeded inputs; then the converted weights run
+through the layer against brute-force classic attention.
+
+Bars: copies, transposes and selector cores are bit-exact.  Products and the higher-order SVD are
+floating point: fp32 storage within 1e-5 relative (the SVD itself runs in fp64 and is compared at
+1e-9 before rounding matters: singular values), bf16 storage within one rounding step of the oracle's
+rounded value."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import classic_attention as ca
+from oracle import conversions as cv
+from oracle import tucker_oracle as orc
+from paper_2603_30033_amd import device as dev
+from paper_2603_30033_amd import workloads as wl
+from paper_2603_30033_amd.device import Layer, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+KEYS = ("C", "U1", "U2", "U3", "Ct", "Ut1", "Ut2", "Ut3")
+
+
+def classic(d, nH, dH, seed, dtype, kv_width=None):
+    host = wl.make_classic_weights(d, nH, dH, seed, dtype, kv_width=kv_width)
+    return host, {k: to_device(v, dtype) for k, v in host.items()}
+
+
+def run_layer(weights, X, dtype, nH, dH, rope_base=None, shared=False):
+    """Forward of the layer with device weights `weights` on host input X [B, N, d]."""
+    r1, r2, r3 = weights["C"].shape
+    t1, t2, t3 = weights["Ct"].shape
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=X.shape[0], N=X.shape[1], d_model=X.shape[2], n_heads=nH, d_head=dH,
+                  r1=r1, r2=r2, r3=r3, rt1=t1, rt2=t2, rt3=t3, dtype=dtype, causal=True, rope_base=rope_base,
+                  shared_kv=shared)
+    with Layer(w, None, device_weights=weights, max_positions=X.shape[1] + 8) as layer:
+        Y = layer.forward(to_device(X, dtype))
+        torch.cuda.synchronize()
+        return to_host(Y)
+
+
+def one_rounding_step(got, ref64, dtype, what):
+    """`got` (storage values as fp32) against the fp64 reference: equal to the reference rounded to the
+    storage type, up to one unit in the last place of that type (the GPU rounds an fp64 or fp32 value
+    that may differ from the oracle's in its last bits)."""
+    ref = wl.round_to_storage(ref64.astype(np.float32), dtype)
+    ulp = {"f32": 2.0 ** -22, "bf16": 2.0 ** -7}[dtype]
+    scale = float(np.max(np.abs(ref64)))
+    bad = np.abs(got - ref) > ulp * np.abs(ref) + 1e-9 * scale
+    assert not bad.any(), f"{what}: {int(bad.sum())} of {bad.size} elements beyond one rounding step"
+
+
+# ---- exact representations -----------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("nG", [4, 2, 1])                        # MHA, GQA, MQA
+def test_gqa_front_end(nG, dtype):
+    d, nH, dH, N = 72, 4, 16, 100
+    host, devw = classic(d, nH, dH, 61, dtype, kv_width=nG * dH)
+    out = dev.from_gqa(devw["WQ"], devw["WK"], devw["WV"], devw["WO"], nH, nG)
+    torch.cuda.synchronize()
+    ref = cv.gqa_to_tucker(host["WQ"], host["WK"], host["WV"], host["WO"], nH, nG)
+    for k in KEYS:
+        assert np.array_equal(to_host(out[k]), ref[k].astype(np.float32)), k
+    X = wl.round_to_storage(np.random.default_rng(62).standard_normal((2, N, d)).astype(np.float32), dtype)
+    y = run_layer(out, X, dtype, nH, dH)
+    for b in range(2):
+        want = ca.gqa_reference(X[b], host["WQ"], host["WK"], host["WV"], host["WO"], nH, nG, causal=True)
+        assert orc.relative_l2(y[b], want) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shared", [False, True])
+def test_mla_front_end_with_coupled_latent_rope(shared, dtype):
+    rng = np.random.default_rng(63)
+    d, nH, dH, N, dcq, dck, base = 96, 6, 16, 130, 40, 24, 1e4
+    g = lambda *sh: wl.round_to_storage((rng.standard_normal(sh) / np.sqrt(sh[0])).astype(np.float32), dtype)
+    h = dict(WDQ=g(d, dcq), WUQ=g(dcq, nH * dH), WDKV=g(d, dck), WUK=g(dck, nH * dH), WUV=g(dck, nH * dH), WO=g(nH * dH, d))
+    if not shared:
+        h["WDV"] = g(d, dck)
+    D = {k: to_device(v, dtype) for k, v in h.items()}
+    out = dev.from_mla(D["WDQ"], D["WUQ"], D["WDKV"], D["WUK"], D.get("WDV"), D["WUV"], D["WO"], nH)
+    torch.cuda.synchronize()
+    ref = cv.mla_to_tucker(h["WDQ"], h["WUQ"], h["WDKV"], h["WUK"], h.get("WDV"), h["WUV"], h["WO"], nH)
+    assert ("Ut3" in out) == (not shared)
+    for k in out:
+        if k == "C":
+            # the only computed array: fp32 accumulation of 16 products, then one rounding
+            got = to_host(out[k])
+            assert orc.relative_l2(got, ref[k]) <= {"f32": 1e-6, "bf16": 4e-3}[dtype]
+            if dtype == "bf16":
+                bad = np.abs(got - ref[k]) > 2.0 ** -8 * np.abs(ref[k]) + 1e-6 * np.abs(ref[k]).max()
+                assert not bad.any()
+        else:
+            assert np.array_equal(to_host(out[k]), ref[k].astype(np.float32)), k
+    # the layer with latent RoPE on these weights against the oracle on the classic weights' own conversion
+    X = wl.round_to_storage(rng.standard_normal((2, N, d)).astype(np.float32), dtype)
+    y = run_layer(out, X, dtype, nH, dH, rope_base=base, shared=shared)
+    full = dict(ref, Ut3=ref["U3"]) if shared else ref
+    want = orc.per_head_forward(X, full, dH, True, base)
+    assert orc.relative_l2(y, want) <= TOL[dtype]
+    # and without RoPE against brute-force MLA
+    y = run_layer(out, X, dtype, nH, dH, shared=shared)
+    want = ca.mla_reference(X[0], h["WDQ"], h["WUQ"], h["WDKV"], h["WUK"], h["WDKV"] if shared else h["WDV"], h["WUV"],
+                            h["WO"], nH, causal=True)
+    assert orc.relative_l2(y[0], want) <= TOL[dtype]
+
+
+# ---- truncated higher-order SVD ------------------------------------------------------------------
+
+def hosvd_case(d, nH, dH, ranks, ranks_t, shared, dtype, seed):
+    host, devw = classic(d, nH, dH, seed, dtype)
+    out, sv = dev.from_mha_hosvd(devw["WQ"], devw["WK"], devw["WV"], devw["WO"], nH, ranks, ranks_t, shared,
+                                 want_singular_values=True)
+    torch.cuda.synchronize()
+    return host, {k: to_host(v) for k, v in out.items()}, np.array(sv), out
+
+
+def oracle_spectra(host, nH):
+    W, Wt = cv.attention_tensors(host["WQ"], host["WK"], host["WV"], host["WO"], nH)
+    return [np.linalg.svd(cv.unfold(T, k), compute_uv=False) for T in (W, Wt) for k in range(3)]
+
+
+def check_spectra(sv, host, nH, d, shared):
+    ref = oracle_spectra(host, nH)
+    parts = np.split(sv, np.cumsum([nH, d, d, nH, d])[:5])
+    for k, (got, want) in enumerate(zip(parts, ref)):
+        if shared and k == 5:
+            assert np.all(got == 0.0)
+            continue
+        assert len(got) == len(want)
+        # the library takes them as square roots of eigenvalues of the Gram matrix, so it is the squares
+        # that carry fp64 accuracy relative to the largest one
+        assert np.max(np.abs(got ** 2 - want ** 2)) <= 1e-11 * want[0] ** 2, k
+        assert np.all(np.diff(got) <= 0)
+
+
+@pytest.mark.parametrize("shape", [
+    dict(d=64, nH=4, dH=16, ranks=(3, 24, 20), ranks_t=(4, 32, 16)),
+    dict(d=72, nH=5, dH=8, ranks=(5, 40, 40), ranks_t=(2, 17, 9)),        # odd head count, ragged tiles
+    dict(d=48, nH=1, dH=24, ranks=(1, 10, 12), ranks_t=(1, 24, 24)),      # one head: a matrix SVD
+    dict(d=320, nH=5, dH=64, ranks=(4, 96, 64), ranks_t=(5, 128, 64)),    # rows longer than one block's first pass
+])
+@pytest.mark.parametrize("shared", [False, True])
+def test_hosvd_front_end_f32_against_the_oracle(shape, shared):
+    d, nH, dH, ranks, ranks_t = (shape[k] for k in ("d", "nH", "dH", "ranks", "ranks_t"))
+    if shared:
+        ranks_t = (ranks_t[0], ranks_t[1], ranks[2])
+    host, got, sv, _ = hosvd_case(d, nH, dH, ranks, ranks_t, shared, "f32", 64)
+    ref = cv.mha_to_tucker_hosvd(host["WQ"], host["WK"], host["WV"], host["WO"], nH, ranks, ranks_t, shared_kv=shared)
+    assert set(got) == set(ref)
+    check_spectra(sv, host, nH, d, shared)
+    for k in ref:
+        scale = float(np.max(np.abs(ref[k])))
+        assert np.max(np.abs(got[k] - ref[k])) <= 1e-5 * scale, k
+    for k in ("U1", "U2", "U3", "Ut1", "Ut2"):                          # orthonormal columns
+        U = got[k].astype(np.float64)
+        assert np.max(np.abs(U.T @ U - np.eye(U.shape[1]))) <= 1e-5, k
+
+
+@pytest.mark.parametrize("shared", [False, True])
+def test_hosvd_front_end_bf16_rounds_the_oracle_values_once(shared):
+    d, nH, dH, ranks, ranks_t = 64, 4, 16, (4, 32, 24), (3, 40, 24)
+    host, got, sv, _ = hosvd_case(d, nH, dH, ranks, ranks_t, shared, "bf16", 65)
+    ref = cv.mha_to_tucker_hosvd(host["WQ"], host["WK"], host["WV"], host["WO"], nH, ranks, ranks_t, shared_kv=shared)
+    check_spectra(sv, host, nH, d, shared)
+    for k in ref:
+        one_rounding_step(got[k], ref[k], "bf16", k)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_hosvd_at_full_ranks_runs_multi_head_attention_through_the_layer(dtype):
+    d, nH, dH, N = 64, 4, 16, 150
+    host, devw = classic(d, nH, dH, 66, dtype)
+    out, _ = dev.from_mha_hosvd(devw["WQ"], devw["WK"], devw["WV"], devw["WO"], nH, (nH, d, d), (nH, d, d))
+    X = wl.round_to_storage(np.random.default_rng(67).standard_normal((2, N, d)).astype(np.float32), dtype)
+    y = run_layer(out, X, dtype, nH, dH)
+    for b in range(2):
+        want = ca.mha_reference(X[b], host["WQ"], host["WK"], host["WV"], host["WO"], nH, causal=True)
+        assert orc.relative_l2(y[b], want) <= TOL[dtype]
+
+
+def test_hosvd_truncated_layer_output_matches_the_oracle_layer_on_oracle_weights():
+    d, nH, dH, N = 96, 6, 16, 120
+    ranks, ranks_t = (4, 48, 32), (6, 64, 32)
+    host, devw = classic(d, nH, dH, 68, "f32")
+    X = np.random.default_rng(69).standard_normal((1, N, d)).astype(np.float32)
+    for shared in (False, True):
+        out, _ = dev.from_mha_hosvd(devw["WQ"], devw["WK"], devw["WV"], devw["WO"], nH, ranks, ranks_t, shared)
+        ref = cv.mha_to_tucker_hosvd(host["WQ"], host["WK"], host["WV"], host["WO"], nH, ranks, ranks_t, shared_kv=shared)
+        full = dict(ref, Ut3=ref["U3"]) if shared else ref
+        y = run_layer(out, X, "f32", nH, dH, rope_base=1e4, shared=shared)
+        assert orc.relative_l2(y, orc.per_head_forward(X, full, dH, True, 1e4)) <= 2e-5
+
+
+def test_hosvd_rejects_ranks_beyond_the_numerical_rank():
+    d, nH, dH = 64, 4, 8                                         # mode-2 rank of W is at most nH*dH = 32
+    host, devw = classic(d, nH, dH, 70, "f32")
+    out = {k: torch.empty(s, device="cuda") for k, s in dict(C=(4, 40, 16), U1=(4, 4), U2=(64, 40), U3=(64, 16), Ct=(4, 16, 16),
+                                                               Ut1=(4, 4), Ut2=(64, 16), Ut3=(64, 16)).items()}
+    ws = torch.empty(dev.ta.tucker_convert_hosvd_workspace_bytes(d, nH, dH), dtype=torch.uint8, device="cuda")
+    st, _ = dev.ta.tucker_convert_from_mha_hosvd(devw["WQ"], devw["WK"], devw["WV"], devw["WO"], nH, (4, 40, 16), (4, 16, 16),
+                                                 False, out, ws, check=False)
+    assert st == -2
+
+
+def gram_of_unfolding(A, B, nH, mode):
+    """sum_i W_i W_i^T (mode 2) or sum_i W_i^T W_i (mode 3) for W_i = A_i B_i^T, from dH-wide pieces."""
+    d, n = A.shape
+    dH = n // nH
+    if mode == 3:
+        A, B = B, A
+    T = np.concatenate([A[:, i * dH:(i + 1) * dH] @ (B[:, i * dH:(i + 1) * dH].T @ B[:, i * dH:(i + 1) * dH])
+                        for i in range(nH)], axis=1)
+    return T @ A.T
+
+
+@pytest.mark.parametrize("name", ["gpt2_small", "llama7b_n4096"])
+def test_hosvd_at_full_model_sizes_by_properties(name):
+    # too large for the dense-tensor oracle: the factors must be orthonormal eigenvectors of the Gram
+    # matrices of the unfoldings (residual against Gram matrices the test forms in fp64), ordered by
+    # eigenvalue, and the core must be the contraction of the tensor with the factors
+    base = wl.WORKLOADS[name]
+    d, nH, dH = base.d_model, base.n_heads, base.d_head
+    ranks = ranks_t = (base.r1, base.r2, base.r3)
+    host, got, sv, _ = hosvd_case(d, nH, dH, ranks, ranks_t, False, "f32", 71)
+    A, B = host["WQ"].astype(np.float64), host["WK"].astype(np.float64)
+    for mode, key, off in ((2, "U2", nH), (3, "U3", nH + d)):
+        M = gram_of_unfolding(A, B, nH, mode)
+        U = got[key].astype(np.float64)
+        lam = sv[off:off + d] ** 2
+        assert np.all(np.diff(lam) <= 0)
+        assert abs(lam.sum() - np.trace(M)) <= 1e-9 * np.trace(M)
+        assert np.max(np.abs(U.T @ U - np.eye(U.shape[1]))) <= 2e-5
+        res = M @ U - U * lam[:U.shape[1]]
+        assert np.linalg.norm(res) <= 1e-5 * lam[0] * np.sqrt(U.shape[1])
+    U1, U2, U3 = (got[k].astype(np.float64) for k in ("U1", "U2", "U3"))
+    P, Q = U2.T @ A, U3.T @ B
+    H = np.stack([P[:, i * dH:(i + 1) * dH] @ Q[:, i * dH:(i + 1) * dH].T for i in range(nH)])
+    C = np.einsum("ia,ibc->abc", U1, H)
+    assert orc.relative_l2(got["C"], C) <= 1e-5
