@@ -128,15 +128,86 @@ def cpu_baseline(w, backward=False):
             "sample": sample, "seconds": round(dt, 3)}
 
 
+def bench_convert_hosvd(w, args):
+    """Time the MHA -> Tucker conversion at the layer shape and ranks of workload `w`."""
+    import numpy as np
+    import torch
+
+    from paper_2603_30033_amd import device as dev
+    from paper_2603_30033_amd import workloads as wl
+
+    d, nH, dH = w.d_model, w.n_heads, w.d_head
+    ranks, ranks_t = (w.r1, w.r2, w.r3), w.ranks_post()
+    log(f"generating MHA weights d={d} nH={nH} dH={dH} ...")
+    host = wl.make_classic_weights(d, nH, dH, w.seed + 7, w.dtype)
+    D = {k: dev.to_device(v, w.dtype) for k, v in host.items()}
+    K, W = args.steps, args.warmup
+    infos = []
+
+    def step():
+        dev.from_mha_hosvd(D["WQ"], D["WK"], D["WV"], D["WO"], nH, ranks, ranks_t, w.shared_kv)
+        infos.append(dev.from_mha_hosvd.last_info)
+
+    for _ in range(W):
+        step()
+    torch.cuda.synchronize()
+    infos.clear()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / K
+    launches = sum(i["jacobi_launches"] for i in infos) / K
+    jac_ms = sum(i["jacobi_ms"] for i in infos) / K
+    jac_bytes = sum(i["jacobi_bytes"] for i in infos) / K
+    ach = jac_bytes / (jac_ms * 1e-3) / 1e9 if jac_ms > 0 else 0.0
+    log(f"{w.name}: {dt:.3f} s per conversion; Jacobi iterations {jac_ms:.1f} ms in {launches:.0f} launches, "
+        f"sweeps {infos[-1]['sweeps']}, {ach:.0f} GB/s")
+    out = {
+        "metric": "hosvd_conversion_seconds", "value": dt, "unit": "s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": dt * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": w.name, "d_model": d, "n_heads": nH, "d_head": dH, "ranks": list(ranks),
+                   "ranks_post": list(ranks_t), "shared_kv": w.shared_kv, "storage": w.dtype},
+        "pass": "convert_hosvd", "sweeps": infos[-1]["sweeps"],
+        "roofline": {"kernel": "jacobi_block_kernel", "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                     "algorithmic_bytes": jac_bytes / max(launches, 1), "avg_us": jac_ms * 1e3 / max(launches, 1),
+                     "launches": launches},
+    }
+    if not args.no_cpu_baseline:
+        # the oracle builds the dense nH x d x d tensors: bounded to a layer of at most 768 channels
+        from threadpoolctl import threadpool_info
+
+        from oracle import conversions as cv
+        ds = min(d, 768)
+        hs = max(1, min(nH, ds // dH))
+        sample = wl.make_classic_weights(ds, hs, dH, w.seed + 7, w.dtype)
+        rs = (min(ranks[0], hs), min(ranks[1], ds), min(ranks[2], ds))
+        rts = (min(ranks_t[0], hs), min(ranks_t[1], ds), min(ranks_t[2], ds))
+        log("timing the CPU oracle on a bounded sample ...")
+        t0 = time.perf_counter()
+        cv.mha_to_tucker_hosvd(sample["WQ"], sample["WK"], sample["WV"], sample["WO"], hs, rs, rts, shared_kv=w.shared_kv)
+        cpu = time.perf_counter() - t0
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        out["cpu_baseline"] = {"value": cpu, "unit": "s", "cores": int(threads), "kind": "oracle",
+                               "sample": f"oracle conversion of a layer with d={ds}, {hs} heads of width {dH} "
+                                         f"(dense tensors, LAPACK SVD of the three unfoldings)"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="llama7b_n4096")
-    ap.add_argument("--pass", dest="which", choices=["forward", "backward", "backward_self_contained"],
+    ap.add_argument("--pass", dest="which",
+                    choices=["forward", "backward", "backward_self_contained", "convert_hosvd"],
                     default="forward",
-                    help="backward: one step = one tucker_attn_backward call on the state a forward call left in "
+                    help="convert_hosvd: one step = one conversion of synthetic MHA weights of the workload's layer "
+                         "shape into Tucker weights of the workload's ranks (tucker_convert_from_mha_hosvd); "
+                         "backward: one step = one tucker_attn_backward call on the state a forward call left in "
                          "the shared workspace (the forward is run once, untimed); backward_self_contained: the "
                          "backward call re-runs the forward inside (prefill workloads only)")
     ap.add_argument("--frozen-weights", action="store_true",
@@ -162,6 +233,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = wl.WORKLOADS[args.workload]
+    if args.which == "convert_hosvd":
+        print(json.dumps(bench_convert_hosvd(w, args)), flush=True)
+        return
     log(f"generating {w.name} ...")
     inp = wl.make_inputs(w)
     K, W = args.steps, args.warmup

@@ -60,6 +60,15 @@ int tucker_convert_from_mla(int32_t dtype, int32_t d, int32_t nH, int32_t dH, in
                             const void *WDV, const void *WUV, const void *WO,
                             const tucker_convert_weights_out *out, void *hip_stream);
 
+/* What one tucker_convert_from_mha_hosvd call did; plain host data. */
+typedef struct {
+  int32_t sweeps[6];        /* Jacobi sweeps of the eigen-problems of W modes 1, 2, 3 and W~ modes 1, 2, 3    */
+                            /* (0: not solved -- one head, or mode 3 of W~ with shared_kv)                    */
+  int64_t jacobi_launches;  /* step kernels launched for the d x d problems (modes 2 and 3)                   */
+  double  jacobi_ms;        /* time of those launches on the stream, from HIP events around each iteration    */
+  double  jacobi_bytes;     /* bytes they read and wrote: every launch rotates all d rows once, 2 * 8 * d * d */
+} tucker_convert_hosvd_info;
+
 /* Bytes of device workspace tucker_convert_from_mha_hosvd needs; 0 if an argument is invalid. */
 size_t tucker_convert_hosvd_workspace_bytes(int32_t d, int32_t nH, int32_t dH);
 
@@ -82,6 +91,7 @@ size_t tucker_convert_hosvd_workspace_bytes(int32_t d, int32_t nH, int32_t dH);
  *               -3 unfoldings of W, then of W~, each in decreasing order (with shared_kv the
  *               last d entries are zero); square roots of Gram eigenvalues, so their squares
  *               are accurate to about 1e-13 of the largest square
+ *   info        HOST, nullable: iteration counts and the time of the dominant kernel
  *   workspace   device, >= tucker_convert_hosvd_workspace_bytes(d, nH, dH), 256-byte aligned
  * Unlike the other entry points this call synchronises hip_stream several times (the iteration
  * count is data dependent) and returns when the results are complete.  A requested rank beyond
@@ -93,7 +103,7 @@ int tucker_convert_from_mha_hosvd(int32_t dtype, int32_t d, int32_t nH, int32_t 
                                   int32_t r1, int32_t r2, int32_t r3,
                                   int32_t rt1, int32_t rt2, int32_t rt3, int32_t shared_kv,
                                   const tucker_convert_weights_out *out, double *singular_values,
-                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+                                  tucker_convert_hosvd_info *info, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

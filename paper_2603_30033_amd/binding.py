@@ -60,6 +60,11 @@ class tucker_convert_weights_out(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in WEIGHT_KEYS]
 
 
+class tucker_convert_hosvd_info(C.Structure):
+    _fields_ = [("sweeps", C.c_int32 * 6), ("jacobi_launches", C.c_int64), ("jacobi_ms", C.c_double),
+                ("jacobi_bytes", C.c_double)]
+
+
 _lib = None
 
 
@@ -116,7 +121,7 @@ def load_library() -> C.CDLL:
     lib.tucker_convert_hosvd_workspace_bytes.argtypes = [C.c_int32] * 3
     lib.tucker_convert_hosvd_workspace_bytes.restype = C.c_size_t
     lib.tucker_convert_from_mha_hosvd.argtypes = [C.c_int32] * 4 + [C.c_void_p] * 4 + [C.c_int32] * 7 + [
-        out_p, C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
+        out_p, C.POINTER(C.c_double), C.POINTER(tucker_convert_hosvd_info), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.tucker_convert_from_mha_hosvd.restype = C.c_int
     _lib = lib
     return lib
@@ -302,13 +307,16 @@ def tucker_convert_hosvd_workspace_bytes(d: int, n_heads: int, d_head: int) -> i
 
 def tucker_convert_from_mha_hosvd(WQ, WK, WV, WO, n_heads: int, ranks, ranks_t, shared_kv: bool, out: Dict,
                                   workspace, want_singular_values: bool = False, stream=None, check: bool = True):
-    """Returns (status, singular values as a list of 2*(nH+2d) floats or None)."""
+    """Returns (status, singular values as a list of 2*(nH+2d) floats or None, info dict)."""
     d, n = WQ.shape
     sv = (C.c_double * (2 * (n_heads + 2 * d)))() if want_singular_values else None
+    info = tucker_convert_hosvd_info()
     st = load_library().tucker_convert_from_mha_hosvd(
         _dtype_code(WQ), d, n_heads, n // n_heads, _ptr(WQ), _ptr(WK), _ptr(WV), _ptr(WO), *[int(r) for r in ranks],
-        *[int(r) for r in ranks_t], int(bool(shared_kv)), C.byref(_out_struct(out)), sv, _ptr(workspace),
+        *[int(r) for r in ranks_t], int(bool(shared_kv)), C.byref(_out_struct(out)), sv, C.byref(info), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream_ptr(stream))
     if check:
         _check(st, "tucker_convert_from_mha_hosvd")
-    return st, (list(sv) if sv is not None else None)
+    return st, (list(sv) if sv is not None else None), dict(
+        sweeps=list(info.sweeps), jacobi_launches=int(info.jacobi_launches), jacobi_ms=float(info.jacobi_ms),
+        jacobi_bytes=float(info.jacobi_bytes))

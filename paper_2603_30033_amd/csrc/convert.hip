@@ -202,65 +202,144 @@ __device__ __forceinline__ void block_sum3(double& a, double& b, double& c, doub
   c = red[0][2] + red[1][2] + red[2][2] + red[3][2];
 }
 
-// One step of a one-sided Jacobi sweep on the rows of G [m, len]: workgroup k takes the k-th
-// pair (p, q) of round `step` of a round-robin tournament over m_pad = m rounded up to even
-// players (pairs of one round are disjoint, so the workgroups touch disjoint rows) and rotates
-// the two rows so that they become orthogonal.  Rows whose squared norm is at most `tiny` are
-// numerically zero and are left alone.  `rotations` counts the pairs that were rotated.
-template <int PER>   // PER > 0: rows of at most 256*PER elements stay in registers between the two passes
-__global__ __launch_bounds__(256) void jacobi_step_kernel(double* G, int m, int len, int step, double tol, double tiny, int* rotations) {
-  __shared__ double red[4][3];
-  const int m_pad = m + (m & 1), n1 = m_pad - 1;
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+
+// One step of a blocked one-sided Jacobi sweep on the rows of G [m, len].  The rows are grouped in
+// blocks of 8; workgroup k takes the k-th pair (P, Q) of round `step` of a round-robin tournament
+// over the blocks (pairs of one round are disjoint, so workgroups touch disjoint rows) and
+//   1. forms the 16 x 16 Gram matrix S = R R^T of its 16 rows with the fp64 matrix instruction
+//      (D[16x16] += A[16x4] B[4x16]; lane l supplies A[l%16][l/16] and B[l/16][l%16], which for
+//      B = A^T is the same register, and receives D[l/16 + 4i][l%16] in register i),
+//   2. runs one cyclic sweep of two-sided Jacobi rotations on S in LDS (15 rounds of 8 disjoint
+//      rotations), accumulating them in V,
+//   3. replaces the rows by V^T R, again with the matrix instruction.
+// A rotation is applied only if the inner product exceeds tol times the LARGER squared norm: that
+// bounds the rotation angle between rows of very different norm (only the leading rows are used
+// afterwards) and equals the usual relative test for rows of similar norm.  Rows whose squared
+// norm is at most `tiny` are numerically zero and are left alone.  Rows >= m of the last block
+// read as zero and are never written.  `rotations` counts the rotations applied.
+template <int NW>   // waves per workgroup: they share the columns in steps 1 and 3; the first four run step 2
+__global__ __launch_bounds__(64 * NW) void jacobi_block_kernel(double* G, int m, int len, int step, double tol, double tiny, int* rotations) {
+  __shared__ double part[NW][16][17];                   // per-wave partial Gram matrices
+  __shared__ double S[2][16][17];                       // double-buffered Gram matrix
+  __shared__ double V[2][16][17];                       // accumulated rotations
+  __shared__ int n_rot;
+  const int nb = (m + 7) / 8, nbp = nb + (nb & 1), n1 = nbp - 1;
   const int k = blockIdx.x;
-  const int p = k == 0 ? n1 : (step + k) % n1;
-  const int q = k == 0 ? step : (step - k + n1) % n1;
-  if (p >= m || q >= m) return;                         // the bye of an odd field
-  double* gp = G + (long)p * len;
-  double* gq = G + (long)q * len;
-  constexpr int R = PER > 0 ? PER : 1;
-  double xp[R], xq[R];
-  double a = 0.0, b = 0.0, c = 0.0;
-  if (PER > 0) {
+  const int P = k == 0 ? n1 : (step + k) % n1;
+  const int Q = k == 0 ? step : (step - k + n1) % n1;
+  // with an odd number of blocks one workgroup per round holds the bye (block index nb): its rows lie
+  // beyond m and read as zero, so the workgroup still rotates the rows of its real block among themselves
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lq = lane >> 4;
+  auto row_of = [&](int r) { return (r < 8 ? P * 8 : Q * 8 - 8) + r; };
+  const int chunks = (len + 15) / 16;
+
+  // 1. Gram matrix: lane (lr, lq) of a wave loads columns c0 + 4 lq .. + 3 of row lr of a 16-column chunk
+  {
+    const int grow = row_of(lr);
+    const double* src = G + (long)grow * len;
+    // four values of this lane's row at columns c .. c+3 (zero beyond the matrix)
+    auto load4 = [&](int ch, double* x) __attribute__((always_inline)) {
+      const int c = ch * 16 + 4 * lq;
+      if (grow < m && c + 3 < len && (len & 1) == 0) {    // even rows start 16-byte aligned
+        const f64x2 lo = *reinterpret_cast<const f64x2*>(src + c), hi = *reinterpret_cast<const f64x2*>(src + c + 2);
+        x[0] = lo[0]; x[1] = lo[1]; x[2] = hi[0]; x[3] = hi[1];
+      } else {
 #pragma unroll
-    for (int e = 0; e < R; ++e) {
-      const int j = threadIdx.x + 256 * e;
-      xp[e] = j < len ? gp[j] : 0.0;
-      xq[e] = j < len ? gq[j] : 0.0;
-      a += xp[e] * xp[e];
-      b += xq[e] * xq[e];
-      c += xp[e] * xq[e];
-    }
-  } else {
-    for (int j = threadIdx.x; j < len; j += 256) {
-      const double u = gp[j], v = gq[j];
-      a += u * u;
-      b += v * v;
-      c += u * v;
-    }
-  }
-  block_sum3(a, b, c, red);
-  if (!(a > tiny) || !(b > tiny) || fabs(c) <= tol * sqrt(a * b)) return;     // uniform over the block
-  // rotation angle that zeroes the inner product: tan(2 theta) = 2c / (a - b)
-  const double zeta = (b - a) / (2.0 * c);
-  const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-  const double cs = 1.0 / sqrt(1.0 + t * t), sn = cs * t;
-  if (PER > 0) {
+        for (int j = 0; j < 4; ++j) x[j] = (grow < m && ch < chunks && c + j < len) ? src[c + j] : 0.0;
+      }
+    };
+    f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+    for (int ch = wave; ch < chunks; ch += 2 * NW) {      // two chunks in flight, two accumulation chains
+      double x0[4], x1[4];
+      load4(ch, x0);
+      load4(ch + NW, x1);                                 // a chunk index beyond the row loads zeros
 #pragma unroll
-    for (int e = 0; e < R; ++e) {
-      const int j = threadIdx.x + 256 * e;
-      if (j < len) {
-        gp[j] = cs * xp[e] - sn * xq[e];
-        gq[j] = sn * xp[e] + cs * xq[e];
+      for (int j = 0; j < 4; ++j) {
+        acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(x0[j], x0[j], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(x1[j], x1[j], acc1, 0, 0, 0);
       }
     }
-  } else {
-    for (int j = threadIdx.x; j < len; j += 256) {
-      const double u = gp[j], v = gq[j];
-      gp[j] = cs * u - sn * v;
-      gq[j] = sn * u + cs * v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) part[wave][lq + 4 * i][lr] = acc0[i] + acc1[i];
+  }
+  if (tid == 0) n_rot = 0;
+  __syncthreads();
+  const int ti = (tid >> 4) & 15, tj = tid & 15;        // this thread's element of S and V (threads 0..255)
+  const bool solver = tid < 256;
+  if (solver) {
+    double sum = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) sum += part[w][ti][tj];
+    S[0][ti][tj] = sum;
+    V[0][ti][tj] = ti == tj ? 1.0 : 0.0;
+  }
+  __syncthreads();
+
+  // 2. one sweep over the 120 pairs of the 16 rows: 15 rounds of 8 disjoint rotations
+  int cur = 0;
+  for (int s = 0; s < 15; ++s) {
+    if (!solver) {                                      // the other waves only keep the barriers company
+      __syncthreads();
+      cur ^= 1;
+      continue;
+    }
+    // coefficients (c, s) with new_x = c * old_x + s * old_partner, for x = ti and x = tj
+    double co[2], si[2];
+    int partner[2];
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+      const int x = w == 0 ? ti : tj;
+      const int y = x == 15 ? s : (x == s ? 15 : (2 * s - x + 30) % 15);
+      partner[w] = y;
+      const int p = x < y ? x : y, q = x < y ? y : x;
+      const double a = S[cur][p][p], b = S[cur][q][q], c = S[cur][p][q];
+      co[w] = 1.0;
+      si[w] = 0.0;
+      if (a > tiny && b > tiny && fabs(c) > tol * fmax(a, b)) {
+        const double zeta = (b - a) / (2.0 * c);
+        const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+        const double cs = 1.0 / sqrt(1.0 + t * t);
+        co[w] = cs;
+        si[w] = x == p ? -cs * t : cs * t;              // row p: cs p - sn q; row q: sn p + cs q
+        if (w == 0 && tj == 0 && x == p) atomicAdd(&n_rot, 1);
+      }
+    }
+    const int pi = partner[0], pj = partner[1];
+    const double snew = co[0] * (co[1] * S[cur][ti][tj] + si[1] * S[cur][ti][pj]) +
+                        si[0] * (co[1] * S[cur][pi][tj] + si[1] * S[cur][pi][pj]);
+    const double vnew = co[1] * V[cur][ti][tj] + si[1] * V[cur][ti][pj];
+    S[cur ^ 1][ti][tj] = snew;
+    V[cur ^ 1][ti][tj] = vnew;
+    __syncthreads();
+    cur ^= 1;
+  }
+  if (n_rot == 0) return;                               // uniform: read after the barrier
+  if (tid == 0) atomicAdd(rotations, n_rot);
+
+  // 3. rows <- V^T R, 16 columns at a time: A[r][k] = V[k][r], B[k][n] = R[k][c0 + n]
+  double va[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) va[kk] = V[cur][4 * kk + lq][lr];
+  for (int ch = wave; ch < chunks; ch += NW) {
+    const int c = ch * 16 + lr;
+    double xb[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int grow = row_of(4 * kk + lq);
+      xb[kk] = (grow < m && c < len) ? G[(long)grow * len + c] : 0.0;
+    }
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(va[kk], xb[kk], acc, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int grow = row_of(lq + 4 * i);
+      if (grow < m && c < len) G[(long)grow * len + c] = acc[i];
     }
   }
-  if (threadIdx.x == 0) atomicAdd(rotations, 1);
 }
 
 // norms2[row] = squared norm of row `row` of G [m, len]
@@ -327,9 +406,17 @@ hipError_t dgemm(hipStream_t s, int batch, int M, int N, int K, const double* A,
 // Eigenvectors of the symmetric positive semi-definite G [m, m] (destroyed) with the r largest
 // eigenvalues -> U64 / U [m, r]; sv (host, nullable) receives the square roots of all
 // eigenvalues in decreasing order.  Synchronises the stream.
+constexpr int kJacobiWaves = 16;
+
+struct JacobiStats {
+  int sweeps = 0;
+  long launches = 0;
+  double ms = 0.0;
+};
+
 template <typename T>
 int leading_eigenvectors(hipStream_t s, double* G, int m, int r, double* norms2, int* idx, int* counter,
-                         double* U64, T* U, double* sv) {
+                         double* U64, T* U, double* sv, JacobiStats* stats) {
   std::vector<double> h(m);
   hipLaunchKernelGGL(row_norms_kernel, dim3(m), dim3(256), 0, s, G, m, norms2);
   CK(hipGetLastError());
@@ -338,22 +425,44 @@ int leading_eigenvectors(hipStream_t s, double* G, int m, int r, double* norms2,
   const double fro2 = std::accumulate(h.begin(), h.end(), 0.0);
   const double tiny = 1e-28 * m * fro2;                 // rows below the rounding noise of G's entries
   const double tol = std::max(2e-15, std::sqrt((double)m) * 2.3e-16);
-  const int m_pad = m + (m & 1);
+  const int nb = (m + 7) / 8, nbp = nb + (nb & 1), n_steps = nbp - 1;   // rounds of the block tournament
   int rotated = 0;
-  for (int sweep = 0; sweep < 60 && m > 1; ++sweep) {
-    CK(hipMemsetAsync(counter, 0, sizeof(int), s));
-    for (int step = 0; step < m_pad - 1; ++step) {
-      if (m <= 256 * 4)
-        hipLaunchKernelGGL((jacobi_step_kernel<4>), dim3(m_pad / 2), dim3(256), 0, s, G, m, m, step, tol, tiny, counter);
-      else if (m <= 256 * 16)
-        hipLaunchKernelGGL((jacobi_step_kernel<16>), dim3(m_pad / 2), dim3(256), 0, s, G, m, m, step, tol, tiny, counter);
-      else
-        hipLaunchKernelGGL((jacobi_step_kernel<0>), dim3(m_pad / 2), dim3(256), 0, s, G, m, m, step, tol, tiny, counter);
+  hipEvent_t ev[2] = {nullptr, nullptr};
+  if (stats) {
+    CK(hipEventCreate(&ev[0]));
+    if (hipEventCreate(&ev[1]) != hipSuccess) {
+      (void)hipEventDestroy(ev[0]);
+      return TUCKER_ATTN_HIP_ERROR;
     }
+    (void)hipEventRecord(ev[0], s);
+  }
+  struct EventGuard {
+    hipEvent_t* e;
+    ~EventGuard() {
+      if (e[0]) (void)hipEventDestroy(e[0]);
+      if (e[1]) (void)hipEventDestroy(e[1]);
+    }
+  } guard{ev};
+  for (int sweep = 0; sweep < 60 && m > 1; ++sweep) {
+    if (stats) {
+      ++stats->sweeps;
+      stats->launches += n_steps;
+    }
+    CK(hipMemsetAsync(counter, 0, sizeof(int), s));
+    for (int step = 0; step < n_steps; ++step)
+      hipLaunchKernelGGL((jacobi_block_kernel<kJacobiWaves>), dim3(nbp / 2), dim3(64 * kJacobiWaves), 0, s, G, m, m, step, tol,
+                         tiny, counter);
     CK(hipGetLastError());
     CK(hipMemcpyAsync(&rotated, counter, sizeof(int), hipMemcpyDeviceToHost, s));
     CK(hipStreamSynchronize(s));
     if (rotated == 0) break;
+  }
+  if (stats) {
+    float ms = 0.f;
+    CK(hipEventRecord(ev[1], s));
+    CK(hipEventSynchronize(ev[1]));
+    CK(hipEventElapsedTime(&ms, ev[0], ev[1]));
+    stats->ms += ms;
   }
   if (rotated != 0) return TUCKER_ATTN_UNSUPPORTED_SHAPE;   // no convergence within the sweep limit
   hipLaunchKernelGGL(row_norms_kernel, dim3(m), dim3(256), 0, s, G, m, norms2);
@@ -416,7 +525,7 @@ HosvdWs carve_hosvd(void* base, int d, int nH, int dH) {
 // ranks.  `given_U3`: the mode-3 factor is already in w.U3 (shared latent) and is not recomputed.
 template <typename T>
 int hosvd_one(hipStream_t s, const HosvdWs& w, int d, int nH, int dH, int r1, int r2, int r3, bool given_U3,
-              T* C, T* U1, T* U2, T* U3, double* sv) {
+              T* C, T* U1, T* U2, T* U3, double* sv, JacobiStats* st3) {
   const long n = (long)nH * dH;
   // per-head dH x dH Gram matrices  SA_i = A_i^T A_i, SB_i = B_i^T B_i
   CK(dgemm(s, nH, dH, dH, d, w.A, 1, n, dH, w.A, n, 1, dH, w.SA, dH, 1, (long)dH * dH));
@@ -426,18 +535,20 @@ int hosvd_one(hipStream_t s, const HosvdWs& w, int d, int nH, int dH, int r1, in
   CK(dgemm(s, 1, (int)n, (int)n, d, w.B, 1, n, 0, w.B, n, 1, 0, w.GB, n, 1, 0));
   hipLaunchKernelGGL(head_gram_kernel, dim3(nH, nH), dim3(256), 0, s, w.GA, w.GB, w.M1, nH, dH);
   CK(hipGetLastError());
-  int st = leading_eigenvectors<T>(s, w.M1, nH, r1, w.norms2, w.idx, w.counter, w.U1, U1, sv);
+  int st = leading_eigenvectors<T>(s, w.M1, nH, r1, w.norms2, w.idx, w.counter, w.U1, U1, sv, st3 ? &st3[0] : nullptr);
   if (st != TUCKER_ATTN_OK) return st;
   // mode 2: sum_i W_i W_i^T = sum_i (A_i SB_i) A_i^T
   CK(dgemm(s, nH, d, dH, dH, w.A, n, 1, dH, w.SB, dH, 1, (long)dH * dH, w.T, n, 1, dH));
   CK(dgemm(s, 1, d, d, (int)n, w.T, n, 1, 0, w.A, 1, n, 0, w.M, d, 1, 0));
-  st = leading_eigenvectors<T>(s, w.M, d, r2, w.norms2, w.idx, w.counter, w.U2, U2, sv ? sv + nH : nullptr);
+  st = leading_eigenvectors<T>(s, w.M, d, r2, w.norms2, w.idx, w.counter, w.U2, U2, sv ? sv + nH : nullptr,
+                                st3 ? &st3[1] : nullptr);
   if (st != TUCKER_ATTN_OK) return st;
   // mode 3: sum_i W_i^T W_i = sum_i (B_i SA_i) B_i^T
   if (!given_U3) {
     CK(dgemm(s, nH, d, dH, dH, w.B, n, 1, dH, w.SA, dH, 1, (long)dH * dH, w.T, n, 1, dH));
     CK(dgemm(s, 1, d, d, (int)n, w.T, n, 1, 0, w.B, 1, n, 0, w.M, d, 1, 0));
-    st = leading_eigenvectors<T>(s, w.M, d, r3, w.norms2, w.idx, w.counter, w.U3, U3, sv ? sv + nH + d : nullptr);
+    st = leading_eigenvectors<T>(s, w.M, d, r3, w.norms2, w.idx, w.counter, w.U3, U3, sv ? sv + nH + d : nullptr,
+                                  st3 ? &st3[2] : nullptr);
     if (st != TUCKER_ATTN_OK) return st;
   } else if (sv) {
     for (int k = 0; k < d; ++k) sv[nH + d + k] = 0.0;
@@ -489,7 +600,26 @@ int from_mla(int d, int nH, int dH, int dcQ, int dcK, const T* WDQ, const T* WUQ
 template <typename T>
 int from_mha_hosvd(int d, int nH, int dH, const T* WQ, const T* WK, const T* WV, const T* WO, int r1, int r2, int r3,
                    int rt1, int rt2, int rt3, bool shared, const tucker_convert_weights_out& o, double* sv,
-                   void* workspace, hipStream_t s) {
+                   tucker_convert_hosvd_info* info, void* workspace, hipStream_t s) {
+  JacobiStats stats[6];
+  struct Report {                                       // filled on every return path
+    tucker_convert_hosvd_info* info;
+    const JacobiStats* st;
+    int d;
+    ~Report() {
+      if (!info) return;
+      info->jacobi_launches = 0;
+      info->jacobi_ms = 0.0;
+      for (int k = 0; k < 6; ++k) {
+        info->sweeps[k] = st[k].sweeps;
+        if (k % 3 != 0) {
+          info->jacobi_launches += st[k].launches;
+          info->jacobi_ms += st[k].ms;
+        }
+      }
+      info->jacobi_bytes = 16.0 * d * d * (double)info->jacobi_launches;
+    }
+  } report{info, stats, d};
   const HosvdWs w = carve_hosvd(workspace, d, nH, dH);
   const long n = (long)nH * dH;
   const int cb = blocks_for((long)d * n);
@@ -497,14 +627,14 @@ int from_mha_hosvd(int d, int nH, int dH, const T* WQ, const T* WK, const T* WV,
   hipLaunchKernelGGL((to_f64_kernel<T>), dim3(cb), dim3(256), 0, s, WQ, n, 1, w.A, d, (int)n);
   hipLaunchKernelGGL((to_f64_kernel<T>), dim3(cb), dim3(256), 0, s, WK, n, 1, w.B, d, (int)n);
   CK(hipGetLastError());
-  int st = hosvd_one<T>(s, w, d, nH, dH, r1, r2, r3, false, (T*)o.C, (T*)o.U1, (T*)o.U2, (T*)o.U3, sv);
+  int st = hosvd_one<T>(s, w, d, nH, dH, r1, r2, r3, false, (T*)o.C, (T*)o.U1, (T*)o.U2, (T*)o.U3, sv, info ? stats : nullptr);
   if (st != TUCKER_ATTN_OK) return st;
   // post-softmax tensor, output index first: A = WO^T, B = WV
   hipLaunchKernelGGL((to_f64_kernel<T>), dim3(cb), dim3(256), 0, s, WO, 1, (long)d, w.A, d, (int)n);
   hipLaunchKernelGGL((to_f64_kernel<T>), dim3(cb), dim3(256), 0, s, WV, n, 1, w.B, d, (int)n);
   CK(hipGetLastError());
   st = hosvd_one<T>(s, w, d, nH, dH, rt1, rt2, rt3, shared, (T*)o.Ct, (T*)o.Ut1, (T*)o.Ut2, (T*)o.Ut3,
-                    sv ? sv + nH + 2 * d : nullptr);
+                    sv ? sv + nH + 2 * d : nullptr, info ? stats + 3 : nullptr);
   if (st != TUCKER_ATTN_OK) return st;
   CK(hipStreamSynchronize(s));
   return TUCKER_ATTN_OK;
@@ -553,7 +683,8 @@ size_t tucker_convert_hosvd_workspace_bytes(int32_t d, int32_t nH, int32_t dH) {
 int tucker_convert_from_mha_hosvd(int32_t dtype, int32_t d, int32_t nH, int32_t dH, const void* WQ, const void* WK,
                                   const void* WV, const void* WO, int32_t r1, int32_t r2, int32_t r3, int32_t rt1,
                                   int32_t rt2, int32_t rt3, int32_t shared_kv, const tucker_convert_weights_out* out,
-                                  double* singular_values, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                                  double* singular_values, tucker_convert_hosvd_info* info, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
   if (dtype != TUCKER_ATTN_F32 && dtype != TUCKER_ATTN_BF16) return TUCKER_ATTN_INVALID_ARG;
   if (d < 1 || nH < 1 || dH < 1) return TUCKER_ATTN_INVALID_ARG;
   if (d > 8192 || nH > 256 || (long)nH * dH > 8192) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
@@ -570,10 +701,10 @@ int tucker_convert_from_mha_hosvd(int32_t dtype, int32_t d, int32_t nH, int32_t 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (dtype == TUCKER_ATTN_F32)
     return ta::from_mha_hosvd<float>(d, nH, dH, (const float*)WQ, (const float*)WK, (const float*)WV, (const float*)WO, r1,
-                                     r2, r3, rt1, rt2, rt3, shared_kv != 0, *out, singular_values, workspace, s);
+                                     r2, r3, rt1, rt2, rt3, shared_kv != 0, *out, singular_values, info, workspace, s);
   return ta::from_mha_hosvd<ta::bf16>(d, nH, dH, (const ta::bf16*)WQ, (const ta::bf16*)WK, (const ta::bf16*)WV,
                                       (const ta::bf16*)WO, r1, r2, r3, rt1, rt2, rt3, shared_kv != 0, *out, singular_values,
-                                      workspace, s);
+                                      info, workspace, s);
 }
 
 }  // extern "C"

@@ -127,7 +127,8 @@ def from_mla(WDQ, WUQ, WDKV, WUK, WDV, WUV, WO, n_heads: int) -> Dict[str, torch
 
 def from_mha_hosvd(WQ, WK, WV, WO, n_heads: int, ranks, ranks_t, shared_kv: bool = False,
                    want_singular_values: bool = False):
-    """Returns (device Tucker weights, singular values or None)."""
+    """Returns (device Tucker weights, singular values or None); the iteration report of the call is kept
+    in `from_mha_hosvd.last_info`."""
     d, n = WQ.shape
     (r1, r2, r3), (t1, t2, t3) = ranks, ranks_t
     shapes = dict(C=(r1, r2, r3), U1=(n_heads, r1), U2=(d, r2), U3=(d, r3), Ct=(t1, t2, t3), Ut1=(n_heads, t1),
@@ -137,6 +138,6 @@ def from_mha_hosvd(WQ, WK, WV, WO, n_heads: int, ranks, ranks_t, shared_kv: bool
     out = _empty_weights(shapes, WQ)
     ws = torch.empty(max(ta.tucker_convert_hosvd_workspace_bytes(d, n_heads, n // n_heads), 256), dtype=torch.uint8,
                      device="cuda")
-    _, sv = ta.tucker_convert_from_mha_hosvd(WQ, WK, WV, WO, n_heads, ranks, ranks_t, shared_kv, out, ws,
-                                             want_singular_values=want_singular_values)
+    _, sv, from_mha_hosvd.last_info = ta.tucker_convert_from_mha_hosvd(
+        WQ, WK, WV, WO, n_heads, ranks, ranks_t, shared_kv, out, ws, want_singular_values=want_singular_values)
     return out, sv

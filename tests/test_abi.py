@@ -44,12 +44,12 @@ def test_conversion_entry_points_reject_bad_arguments_on_the_host():
     assert nbytes > 0 and nbytes % 256 == 0
     hosvd = lambda *a: lib.tucker_convert_from_mha_hosvd(*a)
     W = [256] * 4
-    assert hosvd(0, 64, 4, 16, *W, 5, 8, 8, 4, 8, 8, 0, o, None, 256, 1 << 40, None) == -1         # r1 > nH
-    assert hosvd(0, 64, 4, 16, *W, 4, 65, 8, 4, 8, 8, 0, o, None, 256, 1 << 40, None) == -1        # r2 > d
-    assert hosvd(0, 64, 4, 16, *W, 4, 8, 8, 4, 8, 4, 1, o, None, 256, 1 << 40, None) == -1         # shared needs rt3 == r3
-    assert hosvd(0, 64, 4, 16, *W, 4, 8, 8, 4, 8, 8, 0, o, None, 256, 16, None) == -3              # workspace too small
-    assert hosvd(0, 64, 4, 16, *W, 4, 8, 8, 4, 8, 8, 0, o, None, 257, 1 << 40, None) == -1         # misaligned workspace
-    assert hosvd(0, 16384, 4, 16, *W, 4, 8, 8, 4, 8, 8, 0, o, None, 256, 1 << 40, None) == -2
+    assert hosvd(0, 64, 4, 16, *W, 5, 8, 8, 4, 8, 8, 0, o, None, None, 256, 1 << 40, None) == -1         # r1 > nH
+    assert hosvd(0, 64, 4, 16, *W, 4, 65, 8, 4, 8, 8, 0, o, None, None, 256, 1 << 40, None) == -1        # r2 > d
+    assert hosvd(0, 64, 4, 16, *W, 4, 8, 8, 4, 8, 4, 1, o, None, None, 256, 1 << 40, None) == -1         # shared needs rt3 == r3
+    assert hosvd(0, 64, 4, 16, *W, 4, 8, 8, 4, 8, 8, 0, o, None, None, 256, 16, None) == -3              # workspace too small
+    assert hosvd(0, 64, 4, 16, *W, 4, 8, 8, 4, 8, 8, 0, o, None, None, 257, 1 << 40, None) == -1         # misaligned workspace
+    assert hosvd(0, 16384, 4, 16, *W, 4, 8, 8, 4, 8, 8, 0, o, None, None, 256, 1 << 40, None) == -2
 
 
 def test_status_strings():

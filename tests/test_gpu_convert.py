@@ -201,7 +201,7 @@ def test_hosvd_rejects_ranks_beyond_the_numerical_rank():
     out = {k: torch.empty(s, device="cuda") for k, s in dict(C=(4, 40, 16), U1=(4, 4), U2=(64, 40), U3=(64, 16), Ct=(4, 16, 16),
                                                                Ut1=(4, 4), Ut2=(64, 16), Ut3=(64, 16)).items()}
     ws = torch.empty(dev.ta.tucker_convert_hosvd_workspace_bytes(d, nH, dH), dtype=torch.uint8, device="cuda")
-    st, _ = dev.ta.tucker_convert_from_mha_hosvd(devw["WQ"], devw["WK"], devw["WV"], devw["WO"], nH, (4, 40, 16), (4, 16, 16),
+    st, _, _ = dev.ta.tucker_convert_from_mha_hosvd(devw["WQ"], devw["WK"], devw["WV"], devw["WO"], nH, (4, 40, 16), (4, 16, 16),
                                                  False, out, ws, check=False)
     assert st == -2
 
