@@ -28,6 +28,8 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     ("llama7b_n4096", "attention"): 183920795,
     ("decode_32k", "decode_attention"): 278178687,
+    ("llama7b_n4096", "attention_bwd_dq+attention_bwd_dkv"): 1027893288,
+    ("llama7b_n4096", "jacobi_block_kernel"): 309868665,
 }
 
 
@@ -171,7 +173,8 @@ def bench_convert_hosvd(w, args):
                    "ranks_post": list(ranks_t), "shared_kv": w.shared_kv, "storage": w.dtype},
         "pass": "convert_hosvd", "sweeps": infos[-1]["sweeps"],
         "roofline": {"kernel": "jacobi_block_kernel", "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS,
-                     "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "jacobi_block_kernel")),
                      "algorithmic_bytes": jac_bytes / max(launches, 1), "avg_us": jac_ms * 1e3 / max(launches, 1),
                      "launches": launches},
     }
@@ -339,7 +342,8 @@ def main():
         alg = fb["attn"] + 2 * fl["qhat"]
         ach = alg / (t_ms * 1e-3) / 1e12
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                "frac": ach / peak, "traffic": None, "algorithmic_flops": alg, "avg_us": t_ms * 1e3}
+                "frac": ach / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)), "algorithmic_flops": alg,
+                "avg_us": t_ms * 1e3}
     elif w.mode == "decode":
         dom = "decode_attention"
         es = 2 if w.dtype == "bf16" else 4
