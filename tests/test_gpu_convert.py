@@ -142,6 +142,8 @@ def check_spectra(sv, host, nH, d, shared):
     dict(d=72, nH=5, dH=8, ranks=(5, 40, 40), ranks_t=(2, 17, 9)),        # odd head count, ragged tiles
     dict(d=48, nH=1, dH=24, ranks=(1, 10, 12), ranks_t=(1, 24, 24)),      # one head: a matrix SVD
     dict(d=320, nH=5, dH=64, ranks=(4, 96, 64), ranks_t=(5, 128, 64)),    # rows longer than one block's first pass
+    dict(d=33, nH=3, dH=5, ranks=(2, 9, 11), ranks_t=(3, 15, 7)),         # odd row length: rows not 16-byte aligned
+    dict(d=130, nH=17, dH=4, ranks=(9, 30, 31), ranks_t=(17, 68, 33)),    # 17 heads: three row blocks, one with the bye
 ])
 @pytest.mark.parametrize("shared", [False, True])
 def test_hosvd_front_end_f32_against_the_oracle(shape, shared):
