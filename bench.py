@@ -216,6 +216,9 @@ def main():
     ap.add_argument("--frozen-weights", action="store_true",
                     help="prepare the operand-layout copies of the weights once, outside the timed region "
                          "(tucker_attn_prepare_weights); the default keeps that step inside every call")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="capture the launches of one step into a HIP graph once and time replays of it (the library "
+                         "only enqueues kernels on the caller's stream, so a step can be captured as it is)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also launch a plain device-to-device copy of this many MiB (three times), so that a "
@@ -303,12 +306,24 @@ def main():
                     ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, w.pos0, None, None, ws)
             units = w.B * w.N
 
+        timed_step = step
+        if args.hip_graph:
+            step()                                              # first call outside the capture
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    step()
+            torch.cuda.current_stream().wait_stream(side)
+            timed_step = graph.replay
         for _ in range(W):
-            step()
+            timed_step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(K):
-            step()
+            timed_step()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         ms = dt / K * 1e3
@@ -371,7 +386,7 @@ def main():
                    "ranks": [w.r1, w.r2, w.r3], "causal": w.causal, "rope_base": w.rope_base, "mode": w.mode,
                    "shared_kv": w.shared_kv},
         "tokens_per_s": units / (ms * 1e-3),
-        "pass": args.which, "frozen_weights": bool(args.frozen_weights),
+        "pass": args.which, "frozen_weights": bool(args.frozen_weights), "hip_graph": bool(args.hip_graph),
         "pct_mfma_peak": 100.0 * tflops / (PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS),
         "hbm_gbs_mandatory": mandatory_bytes(w) / (ms * 1e-3) / 1e9,
         "algorithmic_gflop": total_flops / 1e9,
