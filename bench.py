@@ -226,7 +226,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py measures the one-GPU hot path only; run it with --gpus 1 "
-            "(how the path would shard across GPUs is described in DESIGN.md)")
+            "(batch, head and sequence sharding are described in the repository's design notes)")
         sys.exit(2)
 
     import numpy as np

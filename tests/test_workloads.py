@@ -48,3 +48,18 @@ def test_bf16_rounding_is_round_to_nearest_even():
     assert np.array_equal(wl.bf16_bits(x), torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
     # ties go to even: 1 + 2^-8 -> 1.0, 1 + 3*2^-8 -> 1 + 2^-6
     assert ours[4097] == 1.0 and ours[4098] == 1.015625
+
+
+def test_classic_weights_are_deterministic_rounded_and_have_a_decaying_spectrum():
+    a = wl.make_classic_weights(96, 6, 16, 5, "bf16")
+    b = wl.make_classic_weights(96, 6, 16, 5, "bf16")
+    assert all(np.array_equal(a[k], b[k]) for k in a)
+    assert a["WQ"].shape == (96, 96) and a["WK"].shape == (96, 96) and a["WO"].shape == (96, 96)
+    g = wl.make_classic_weights(96, 6, 16, 5, "bf16", kv_width=32)
+    assert g["WK"].shape == (96, 32) and g["WV"].shape == (96, 32) and g["WQ"].shape == (96, 96)
+    for k in a:                                                   # values the storage type holds exactly
+        assert np.array_equal(wl.round_to_storage(a[k], "bf16"), a[k]), k
+    f = wl.make_classic_weights(96, 6, 16, 5, "f32")
+    assert abs(np.mean(np.sum(f["WQ"].astype(np.float64) ** 2, axis=0)) - 1.0) < 0.2   # unit expected column norm
+    s = np.linalg.svd(f["WQ"].astype(np.float64), compute_uv=False)
+    assert s[0] / s[47] > 4.0 and np.all(np.diff(s) <= 0)         # power-law weighting, not a flat Gaussian spectrum
