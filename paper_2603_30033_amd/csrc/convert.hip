@@ -214,9 +214,8 @@ typedef double f64x2 __attribute__((ext_vector_type(2)));
 //   2. runs one cyclic sweep of two-sided Jacobi rotations on S in LDS (15 rounds of 8 disjoint
 //      rotations), accumulating them in V,
 //   3. replaces the rows by V^T R, again with the matrix instruction.
-// A rotation is applied only if the inner product exceeds tol times the LARGER squared norm: that
-// bounds the rotation angle between rows of very different norm (only the leading rows are used
-// afterwards) and equals the usual relative test for rows of similar norm.  Rows whose squared
+// A rotation is applied only if the inner product exceeds tol times the product of the two norms (the
+// relative test, which keeps the small rows accurate relative to their own size).  Rows whose squared
 // norm is at most `tiny` are numerically zero and are left alone.  Rows >= m of the last block
 // read as zero and are never written.  `rotations` counts the rotations applied.
 template <int NW>   // waves per workgroup: they share the columns in steps 1 and 3; the first four run step 2
@@ -298,7 +297,7 @@ __global__ __launch_bounds__(64 * NW) void jacobi_block_kernel(double* G, int m,
       const double a = S[cur][p][p], b = S[cur][q][q], c = S[cur][p][q];
       co[w] = 1.0;
       si[w] = 0.0;
-      if (a > tiny && b > tiny && fabs(c) > tol * fmax(a, b)) {
+      if (a > tiny && b > tiny && fabs(c) > tol * sqrt(a * b)) {
         const double zeta = (b - a) / (2.0 * c);
         const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
         const double cs = 1.0 / sqrt(1.0 + t * t);
