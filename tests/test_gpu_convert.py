@@ -243,3 +243,21 @@ def test_hosvd_at_full_model_sizes_by_properties(name):
     H = np.stack([P[:, i * dH:(i + 1) * dH] @ Q[:, i * dH:(i + 1) * dH].T for i in range(nH)])
     C = np.einsum("ia,ibc->abc", U1, H)
     assert orc.relative_l2(got["C"], C) <= 1e-5
+
+
+def test_gpt2_sized_layer_converted_on_the_gpu_runs_like_the_oracle_layer_on_oracle_converted_weights():
+    # the whole switch at a real layer shape: MHA weights -> Tucker weights of the paper's GPT-2 ranks on the
+    # GPU, then the bf16 layer; reference: oracle conversion (dense tensors, LAPACK) and oracle layer in fp64
+    base = wl.WORKLOADS["gpt2_small"]
+    d, nH, dH = base.d_model, base.n_heads, base.d_head
+    ranks = (base.r1, base.r2, base.r3)
+    host, devw = classic(d, nH, dH, 74, "bf16")
+    out, _ = dev.from_mha_hosvd(devw["WQ"], devw["WK"], devw["WV"], devw["WO"], nH, ranks, ranks)
+    ref = cv.mha_to_tucker_hosvd(host["WQ"], host["WK"], host["WV"], host["WO"], nH, ranks, ranks)
+    for k in ref:
+        one_rounding_step(to_host(out[k]), ref[k], "bf16", k)
+    X = wl.round_to_storage(np.random.default_rng(75).standard_normal((2, 333, d)).astype(np.float32), "bf16")
+    y = run_layer(out, X, "bf16", nH, dH, rope_base=base.rope_base)
+    stored = {k: wl.round_to_storage(v.astype(np.float32), "bf16") for k, v in ref.items()}
+    want = orc.per_head_forward(X, stored, dH, True, base.rope_base)
+    assert orc.relative_l2(y, want) <= TOL["bf16"]
