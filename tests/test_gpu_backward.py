@@ -200,3 +200,11 @@ def test_backward_head_rank_one(dtype):
         bar = 6e-2 if (dtype == "bf16" and k in ("dU1", "dUt1")) else TOL[dtype]
         err = orc.relative_l2(got[k], ref[k])
         assert err <= bar, (k, err)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_at_maximum_ranks(dtype):
+    # r1 = 64, r2 = 512, r3 = 128 before and after the softmax, 64 heads
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=1, N=70, n_heads=64, d_model=256, d_head=64, r1=64, r2=512, r3=128,
+                  rt1=64, rt2=512, rt3=128, dtype=dtype, seed=41, recipe="fan_in")
+    run_case(w)

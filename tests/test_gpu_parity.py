@@ -335,6 +335,17 @@ def test_unequal_and_unaligned_ranks_and_odd_head_count(dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_maximum_ranks_and_head_count(dtype):
+    # every rank at the limit the library states: r1 = 64, r2 = 512, r3 = 128 (and the same after the softmax), 64 heads
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=1, N=70, n_heads=64, d_model=256, d_head=64, r1=64, r2=512, r3=128,
+                  rt1=64, rt2=512, rt3=128, dtype=dtype, seed=12, recipe="fan_in")
+    inp = wl.make_inputs(w)
+    check(run_forward(w, inp), oracle_forward(w, inp), dtype, "maximum ranks, prefill")
+    wd = wl.scaled(w, B=3, N=1, mode="decode", kv_len=150, seed=13)
+    check_decode(wd, wl.make_inputs(wd), "maximum ranks, decode")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_position_offset_and_cache_outputs(dtype):
     w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=90, dtype=dtype, seed=11)
     inp = wl.make_inputs(w)
