@@ -334,6 +334,21 @@ def test_unequal_and_unaligned_ranks_and_odd_head_count(dtype):
     check(run_forward(w, inp), oracle_forward(w, inp), dtype, "wide ranks")
 
 
+def test_long_sequences():
+    # 16k-token prefill (sampled rows) and a 128k-token cache in decode, both at the LLaMA-7B layer shape
+    w = wl.scaled(wl.WORKLOADS["llama7b_n4096"], B=1, N=16384, seed=14)
+    inp = wl.make_inputs(w)
+    rows = [0, 63, 64, 4095, 8192, 12345, 16382, 16383]
+    y = run_forward(w, inp)
+    check(y[:, rows], oracle_forward(w, inp, rows=rows), w.dtype, "N=16384")
+    wd = wl.scaled(wl.WORKLOADS["decode_32k"], B=2, kv_len=131072, seed=15)
+    ind = wl.make_inputs(wd)
+    ind["kv_len"] = np.array([131072, 100003], dtype=ind["kv_len"].dtype)
+    ind["Kcache"][1, 100002:] = 0
+    ind["Vcache"][1, 100002:] = 0
+    check_decode(wd, ind, "128k-token cache")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_maximum_ranks_and_head_count(dtype):
     # every rank at the limit the library states: r1 = 64, r2 = 512, r3 = 128 (and the same after the softmax), 64 heads
