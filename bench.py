@@ -205,6 +205,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="llama7b_n4096")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's number of sequences")
+    ap.add_argument("--seq-len", type=int, default=0,
+                    help="override the workload's tokens per sequence (prefill) or cache length (decode)")
     ap.add_argument("--pass", dest="which",
                     choices=["forward", "backward", "backward_self_contained", "convert_hosvd"],
                     default="forward",
@@ -239,6 +242,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = wl.WORKLOADS[args.workload]
+    if args.batch > 0:
+        w = wl.scaled(w, B=args.batch, name=f"{w.name}_B{args.batch}")
+    if args.seq_len > 0:
+        w = wl.scaled(w, name=f"{w.name}_L{args.seq_len}",
+                      **({"kv_len": args.seq_len} if w.mode == "decode" else {"N": args.seq_len}))
     if args.which == "convert_hosvd":
         print(json.dumps(bench_convert_hosvd(w, args)), flush=True)
         return
