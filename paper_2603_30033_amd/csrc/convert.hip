@@ -212,7 +212,7 @@ typedef double f64x2 __attribute__((ext_vector_type(2)));
 //      (D[16x16] += A[16x4] B[4x16]; lane l supplies A[l%16][l/16] and B[l/16][l%16], which for
 //      B = A^T is the same register, and receives D[l/16 + 4i][l%16] in register i),
 //   2. runs one cyclic sweep of two-sided Jacobi rotations on S in LDS (15 rounds of 8 disjoint
-//      rotations), accumulating them in V,
+//      rotations, worked out once per round), accumulating them in V,
 //   3. replaces the rows by V^T R, again with the matrix instruction.
 // A rotation is applied only if the inner product exceeds tol times the product of the two norms (the
 // relative test, which keeps the small rows accurate relative to their own size).  Rows whose squared
@@ -277,41 +277,37 @@ __global__ __launch_bounds__(64 * NW) void jacobi_block_kernel(double* G, int m,
   }
   __syncthreads();
 
-  // 2. one sweep over the 120 pairs of the 16 rows: 15 rounds of 8 disjoint rotations
+  // 2. one sweep over the 120 pairs of the 16 rows: 15 rounds of 8 disjoint rotations.  Eight threads work
+  // out the rotations of a round (new_x = co[x] old_x + si[x] old_partner), then the 256 solver threads
+  // update their elements of S and V; the other waves only keep the barriers company.
+  __shared__ double co[16], si[16];
   int cur = 0;
   for (int s = 0; s < 15; ++s) {
-    if (!solver) {                                      // the other waves only keep the barriers company
-      __syncthreads();
-      cur ^= 1;
-      continue;
-    }
-    // coefficients (c, s) with new_x = c * old_x + s * old_partner, for x = ti and x = tj
-    double co[2], si[2];
-    int partner[2];
-#pragma unroll
-    for (int w = 0; w < 2; ++w) {
-      const int x = w == 0 ? ti : tj;
-      const int y = x == 15 ? s : (x == s ? 15 : (2 * s - x + 30) % 15);
-      partner[w] = y;
+    if (tid < 8) {
+      const int x = tid == 0 ? 15 : (s + tid) % 15, y = tid == 0 ? s : (s - tid + 15) % 15;
       const int p = x < y ? x : y, q = x < y ? y : x;
       const double a = S[cur][p][p], b = S[cur][q][q], c = S[cur][p][q];
-      co[w] = 1.0;
-      si[w] = 0.0;
+      double cs = 1.0, sn = 0.0;
       if (a > tiny && b > tiny && fabs(c) > tol * sqrt(a * b)) {
         const double zeta = (b - a) / (2.0 * c);
         const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-        const double cs = 1.0 / sqrt(1.0 + t * t);
-        co[w] = cs;
-        si[w] = x == p ? -cs * t : cs * t;              // row p: cs p - sn q; row q: sn p + cs q
-        if (w == 0 && tj == 0 && x == p) atomicAdd(&n_rot, 1);
+        cs = 1.0 / sqrt(1.0 + t * t);
+        sn = cs * t;
+        atomicAdd(&n_rot, 1);
       }
+      co[p] = cs; si[p] = -sn;                            // row p: cs p - sn q
+      co[q] = cs; si[q] = sn;                             // row q: sn p + cs q
     }
-    const int pi = partner[0], pj = partner[1];
-    const double snew = co[0] * (co[1] * S[cur][ti][tj] + si[1] * S[cur][ti][pj]) +
-                        si[0] * (co[1] * S[cur][pi][tj] + si[1] * S[cur][pi][pj]);
-    const double vnew = co[1] * V[cur][ti][tj] + si[1] * V[cur][ti][pj];
-    S[cur ^ 1][ti][tj] = snew;
-    V[cur ^ 1][ti][tj] = vnew;
+    __syncthreads();
+    if (solver) {
+      const int pi = ti == 15 ? s : (ti == s ? 15 : (2 * s - ti + 30) % 15);
+      const int pj = tj == 15 ? s : (tj == s ? 15 : (2 * s - tj + 30) % 15);
+      const double ci = co[ti], zi = si[ti], cj = co[tj], zj = si[tj];
+      const double snew = ci * (cj * S[cur][ti][tj] + zj * S[cur][ti][pj]) + zi * (cj * S[cur][pi][tj] + zj * S[cur][pi][pj]);
+      const double vnew = cj * V[cur][ti][tj] + zj * V[cur][ti][pj];
+      S[cur ^ 1][ti][tj] = snew;
+      V[cur ^ 1][ti][tj] = vnew;
+    }
     __syncthreads();
     cur ^= 1;
   }
