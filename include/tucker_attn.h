@@ -102,6 +102,21 @@ typedef struct {
  */
 int tucker_attn_create(const tucker_attn_config *cfg, tucker_attn_ctx **out);
 
+/*
+ * Memory footprint of the layer (table "Comparison of the memory footprint of MHA, MQA, GQA, MLA and
+ * Tucker Attention"), host arithmetic only.
+ *   tucker_attn_parameter_count   number of weights of one layer: the two cores, the two head factors and
+ *                                 the query / key / output / value factors, nH r1 + d (r2 + r3) + r1 r2 r3 for
+ *                                 the pre-softmax tensor plus the same with the post-softmax ranks; with
+ *                                 shared_kv the value factor is not counted (it is the key factor).  0 if
+ *                                 cfg is NULL.
+ *   tucker_attn_cache_bytes       bytes of latent KV cache the caller allocates for B sequences of up to
+ *                                 Lmax tokens: B * Lmax * (r3 + rt3) elements of the storage type, B * Lmax * r3
+ *                                 with shared_kv.  0 if an argument is invalid.
+ */
+size_t tucker_attn_parameter_count(const tucker_attn_config *cfg);
+size_t tucker_attn_cache_bytes(const tucker_attn_ctx *ctx, int32_t B, int32_t Lmax);
+
 /* Free the context and its rotation table.  NULL is ignored. */
 void tucker_attn_destroy(tucker_attn_ctx *ctx);
 

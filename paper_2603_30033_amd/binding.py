@@ -17,7 +17,8 @@ TUCKER_ATTN_F32 = 0
 TUCKER_ATTN_BF16 = 1
 
 EXPORTED = [
-    "tucker_attn_create", "tucker_attn_destroy", "tucker_attn_workspace_bytes",
+    "tucker_attn_create", "tucker_attn_destroy", "tucker_attn_parameter_count", "tucker_attn_cache_bytes",
+    "tucker_attn_workspace_bytes",
     "tucker_attn_decode_workspace_bytes", "tucker_attn_forward", "tucker_attn_decode",
     "tucker_attn_backward_workspace_bytes", "tucker_attn_backward",
     "tucker_attn_prepared_weights_bytes", "tucker_attn_prepare_weights", "tucker_attn_release_weights",
@@ -83,6 +84,10 @@ def load_library() -> C.CDLL:
     lib.tucker_attn_create.restype = C.c_int
     lib.tucker_attn_destroy.argtypes = [ctx_p]
     lib.tucker_attn_destroy.restype = None
+    lib.tucker_attn_parameter_count.argtypes = [C.POINTER(tucker_attn_config)]
+    lib.tucker_attn_parameter_count.restype = C.c_size_t
+    lib.tucker_attn_cache_bytes.argtypes = [ctx_p, C.c_int32, C.c_int32]
+    lib.tucker_attn_cache_bytes.restype = C.c_size_t
     lib.tucker_attn_workspace_bytes.argtypes = [ctx_p, C.c_int32, C.c_int32]
     lib.tucker_attn_workspace_bytes.restype = C.c_size_t
     lib.tucker_attn_decode_workspace_bytes.argtypes = [ctx_p, C.c_int32]
@@ -161,6 +166,16 @@ def tucker_attn_create(*, d_model, n_heads, d_head, r1, r2, r3, rt1=None, rt2=No
 
 def tucker_attn_destroy(ctx: int) -> None:
     load_library().tucker_attn_destroy(ctx)
+
+
+def tucker_attn_parameter_count(*, d_model, n_heads, r1, r2, r3, rt1=None, rt2=None, rt3=None, shared_kv=False) -> int:
+    cfg = tucker_attn_config(d_model, n_heads, 1, r1, r2, r3, rt1 or r1, rt2 or r2, rt3 or r3, 0, 0, 0.0, TUCKER_ATTN_BF16,
+                             1, int(bool(shared_kv)), 0)
+    return int(load_library().tucker_attn_parameter_count(C.byref(cfg)))
+
+
+def tucker_attn_cache_bytes(ctx: int, B: int, Lmax: int) -> int:
+    return int(load_library().tucker_attn_cache_bytes(ctx, B, Lmax))
 
 
 def tucker_attn_workspace_bytes(ctx: int, B: int, N: int) -> int:

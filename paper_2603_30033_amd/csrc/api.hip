@@ -396,6 +396,20 @@ void tucker_attn_destroy(tucker_attn_ctx* c) {
   delete c;
 }
 
+size_t tucker_attn_parameter_count(const tucker_attn_config* f) {
+  if (!f) return 0;
+  const size_t d = f->d_model, nH = f->n_heads;
+  const size_t pre = nH * f->r1 + d * ((size_t)f->r2 + f->r3) + (size_t)f->r1 * f->r2 * f->r3;
+  const size_t post = nH * f->rt1 + d * ((size_t)f->rt2 + (f->shared_kv ? 0 : f->rt3)) + (size_t)f->rt1 * f->rt2 * f->rt3;
+  return pre + post;
+}
+
+size_t tucker_attn_cache_bytes(const tucker_attn_ctx* c, int32_t B, int32_t Lmax) {
+  if (!c || B < 1 || Lmax < 1) return 0;
+  const tucker_attn_config& f = c->cfg;
+  return (size_t)B * Lmax * ((size_t)f.r3 + (f.shared_kv ? 0 : f.rt3)) * c->es;
+}
+
 size_t tucker_attn_workspace_bytes(const tucker_attn_ctx* c, int32_t B, int32_t N) {
   if (!c || B < 1 || N < 1) return 0;
   if (c->cfg.save_for_backward) return carve_backward(c, nullptr, B, N).bytes;

@@ -121,3 +121,33 @@ def test_shared_kv_config_is_validated_on_the_host():
     assert "status -1 " in str(e.value)
     ctx = ta.tucker_attn_create(**_cfg(shared_kv=True))
     ta.tucker_attn_destroy(ctx)
+
+
+def test_memory_footprint_helpers_match_the_closed_forms_and_the_printed_gpt2_figures():
+    from oracle import sizes
+    d, nH, layers, N = 768, 12, 12, 1024
+    # GPT-2 table of the paper: attention parameters and KV cache in MB (bf16, 12 layers, N = 1024)
+    for ranks, p_mb, kv_mb in (((8, 128, 128), 15.74, 6.28), ((8, 128, 64), 10.24, 3.14), ((8, 64, 64), 6.31, 3.14)):
+        r1, r2, r3 = ranks
+        n = ta.tucker_attn_parameter_count(d_model=d, n_heads=nH, r1=r1, r2=r2, r3=r3)
+        assert n == sizes.tucker_params(d, nH, r1, r2, r3)
+        assert abs(n * 2 * layers / 1e6 - p_mb) < 0.01
+        ctx = ta.tucker_attn_create(**_cfg(d_model=d, n_heads=nH, r1=r1, r2=r2, r3=r3, dtype="bf16", max_positions=N))
+        try:
+            b = ta.tucker_attn_cache_bytes(ctx, 1, N)
+            assert b == sizes.tucker_cache(N, r3) * 2
+            assert abs(b * layers / 1e6 - kv_mb) < 0.02            # the table prints 6.28 for 6.2915
+            assert ta.tucker_attn_cache_bytes(ctx, 0, N) == 0 and ta.tucker_attn_cache_bytes(ctx, 1, 0) == 0
+        finally:
+            ta.tucker_attn_destroy(ctx)
+    # shared key-value latent: one d x r3 factor and one cache fewer; separate post-softmax ranks
+    assert ta.tucker_attn_parameter_count(d_model=d, n_heads=nH, r1=8, r2=128, r3=128, shared_kv=True) == \
+        sizes.tucker_params(d, nH, 8, 128, 128, True)
+    assert ta.tucker_attn_parameter_count(d_model=64, n_heads=4, r1=2, r2=8, r3=16, rt1=3, rt2=24, rt3=32) == \
+        (4 * 2 + 64 * (8 + 16) + 2 * 8 * 16) + (4 * 3 + 64 * (24 + 32) + 3 * 24 * 32)
+    ctx = ta.tucker_attn_create(**_cfg(r3=32, shared_kv=True, dtype="f32"))
+    try:
+        assert ta.tucker_attn_cache_bytes(ctx, 3, 100) == 3 * 100 * 32 * 4
+    finally:
+        ta.tucker_attn_destroy(ctx)
+    assert ta.load_library().tucker_attn_parameter_count(None) == 0
