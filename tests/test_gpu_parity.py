@@ -514,3 +514,36 @@ def test_prepared_weights_in_decode():
         y1 = layer.decode(x, Kc1, Vc1, inp["kv_len"]).clone()
         torch.cuda.synchronize()
         assert torch.equal(y0, y1) and torch.equal(Kc0, Kc1) and torch.equal(Vc0, Vc1)
+
+
+def test_forward_replays_correctly_from_a_hip_graph():
+    # the library only enqueues kernels on the caller's stream, so a call can be captured; every replay,
+    # with fresh inputs copied into the captured buffers and eager work in between, must equal the eager result
+    w = wl.scaled(wl.WORKLOADS["gpt2_small"], B=2, N=200)
+    inp = wl.make_inputs(w)
+    rng = np.random.default_rng(77)
+    with Layer(w, inp, max_positions=w.N + 8) as layer:
+        X = to_device(inp["X"], w.dtype)
+        Y = torch.empty_like(X)
+        ws = layer.workspace(ta.tucker_attn_workspace_bytes(layer.ctx, w.B, w.N))
+        ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, 0, None, None, ws)      # first call outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                ta.tucker_attn_forward(layer.ctx, layer.weights, X, Y, 0, None, None, ws)
+        torch.cuda.current_stream().wait_stream(side)
+        for rep in range(4):
+            Xn = wl.round_to_storage(rng.standard_normal(inp["X"].shape).astype(np.float32), w.dtype)
+            X.copy_(to_device(Xn, w.dtype))
+            Y.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            got = to_host(Y)
+            Ye = torch.empty_like(X)
+            ta.tucker_attn_forward(layer.ctx, layer.weights, X, Ye, 0, None, None, ws)  # eager, same workspace
+            torch.cuda.synchronize()
+            assert np.array_equal(got, to_host(Ye)), f"replay {rep}"
+            check(got, orc.per_head_forward(Xn, wl.weights_of(inp), w.d_head, w.causal, w.rope_base), w.dtype, f"replay {rep}")
