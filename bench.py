@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # WRITE_SIZE runs summarised in profiles/hbm_traffic_<workload>.md, scaled by what the same counters
 # read for a plain 256 MiB copy (factors 1.9998 and 1.0000).  Workloads without a counter run report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("llama7b_n4096", "attention"): 183920795,
+    ("llama7b_n4096", "attention"): 132690388,
     ("decode_32k", "decode_attention"): 278178687,
     ("llama7b_n4096", "attention_bwd_dq+attention_bwd_dkv"): 1027893288,
     ("llama7b_n4096", "jacobi_block_kernel"): 309868665,

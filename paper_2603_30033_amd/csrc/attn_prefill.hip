@@ -48,8 +48,13 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
   // dispatched heavy (late causal tiles) first, and those running together read the same keys
   const int qt = n_qtiles - 1 - blockIdx.y;
   const int n_hg = (p.nH + HW - 1) / HW;
-  const int b = blockIdx.x / n_hg;
-  const int head_raw = (blockIdx.x % n_hg) * HW + wave / QW;
+  // Workgroups are dealt to the 8 XCDs (each with its own L2) in turn.  The (sequence, head group) items of a
+  // row are therefore re-indexed so that one XCD gets neighbouring items: it then sees the K/V of as few
+  // sequences as possible, and those stay in its L2 for all the head groups and query tiles that read them.
+  int item = blockIdx.x;
+  if (gridDim.x % 8 == 0) item = (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
+  const int b = item / n_hg;
+  const int head_raw = (item % n_hg) * HW + wave / QW;
   const bool head_ok = head_raw < p.nH;
   const int head = head_ok ? head_raw : p.nH - 1;
   const int t0 = qt * TQ;                                       // first token of the workgroup
