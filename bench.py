@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     ("llama7b_n4096", "attention"): 132690388,
     ("decode_32k", "decode_attention"): 278178687,
-    ("llama7b_n4096", "attention_bwd_dq+attention_bwd_dkv"): 1027893288,
+    ("llama7b_n4096", "attention_bwd_dq+attention_bwd_dkv"): 955861929,
     ("llama7b_n4096", "jacobi_block_kernel"): 309868665,
 }
 

@@ -102,8 +102,12 @@ __global__ __launch_bounds__(512) void bwd_dq_kernel(BwdArgs p) {
   const int n_qtiles = p.Npad / TQ;
   const int qt = n_qtiles - 1 - blockIdx.y;                     // heavy (late causal) tiles first
   const int n_hg = (p.nH + HW - 1) / HW;
-  const int b = blockIdx.x / n_hg;
-  const int head_raw = (blockIdx.x % n_hg) * HW + wave % HW;
+  // consecutive workgroups go to the 8 XCDs in turn: re-index the (sequence, head group) items of a row so
+  // that one XCD, with its own L2, gets neighbouring items and sees the K/V of as few sequences as possible
+  int item = blockIdx.x;
+  if (gridDim.x % 8 == 0) item = (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
+  const int b = item / n_hg;
+  const int head_raw = (item % n_hg) * HW + wave % HW;
   const bool head_ok = head_raw < p.nH;
   const int head = head_ok ? head_raw : p.nH - 1;
   const int t0 = qt * TQ;
