@@ -328,7 +328,9 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[qb][nb][e] = fast_exp2(s[qb][nb][e]);
         pf[qb][nb] = to_frag<T>(s[qb][nb]);
-        l_run[qb] += block_sum(s[qb][nb]);
+        // 128 channels keep the matrix pipe busy: keep the row sum off it
+        if constexpr (D >= 128) l_run[qb] = block_sum(s[qb][nb], l_run[qb]);
+        else l_run[qb] = frag_sum(pf[qb][nb], l_run[qb]);
       }
     }
   };

@@ -284,17 +284,37 @@ __device__ __forceinline__ void store1(bf16* p, float a) { *p = (bf16)a; }
 __device__ __forceinline__ float to_f32(float a) { return a; }
 __device__ __forceinline__ float to_f32(bf16 a) { return (float)a; }
 
-// Sum of the 16 elements of an accumulator block, pairwise, in plain fp32 adds.  (The packed dot
-// product v_dot2c_f32_bf16 would add two rounded probabilities per instruction, but it runs on the
-// matrix pipe: measured on gfx950, one of them between two MFMAs stretches the pair from 17 to 30 ns,
-// and from a partner wave it stalls that wave behind every MFMA in flight.)
-__device__ __forceinline__ float block_sum(const f32x16& a) {
+// Row-sum pieces of the softmax: the 16 probabilities a lane holds of one 32x32 block, added to acc.
+// block_sum: the unrounded fp32 values, pairwise, in plain v_add_f32.
+// frag_sum (bf16): the rounded values, two per v_dot2c_f32_bf16 -- half the instructions, but that
+// instruction runs on the matrix pipe: measured on gfx950, one of them between two MFMAs stretches the
+// pair from 17 to 30 ns, and issued by the partner wave it waits behind every MFMA in flight.  It pays
+// only where the matrix pipe has idle time (the 32- and 64-channel kernels); see the call site.
+__device__ __forceinline__ float block_sum(const f32x16& a, float acc) {
   float t[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) t[i] = a[2 * i] + a[2 * i + 1];
 #pragma unroll
   for (int i = 0; i < 4; ++i) t[i] = t[2 * i] + t[2 * i + 1];
-  return (t[0] + t[1]) + (t[2] + t[3]);
+  return acc + ((t[0] + t[1]) + (t[2] + t[3]));
+}
+__device__ __forceinline__ float frag_sum(const Frag<float>& f, float acc) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc += f.v[i][j];
+  return acc;
+}
+__device__ __forceinline__ float frag_sum(const Frag<bf16>& f, float acc) {
+  const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      bf16x2 pr = {f.v[i][2 * j], f.v[i][2 * j + 1]};
+      acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
+    }
+  return acc;
 }
 
 // 16-byte chunk of T elements
