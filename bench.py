@@ -117,7 +117,7 @@ def cpu_baseline(w, backward=False):
         sample = f"full oracle backward of {b} sequence(s) of {n} tokens of the same layer shape"
     else:
         n = min(w.N, 4096)
-        b = 1 if w.N >= 1024 else min(w.B, 16)
+        b = min(w.B, 2) if w.N >= 1024 else min(w.B, 16)        # about 10 s of host time at the LLaMA-7B shape
         ws = wl.scaled(w, B=b, N=n)
         inp = wl.make_inputs(ws)
         t0 = time.perf_counter()
