@@ -255,6 +255,9 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
       return frag_swz(kbase + (j / CB) * 32 * L::kKRowElems, (j % CB) * 2 * FC + h * FC, xk);
     };
     Frag<T> ring[kRing];
+    // the partner wave of the SIMD is in its softmax or staging phase meanwhile: matrix work goes first
+    // (268 against 273 us at 4096 tokens; the reverse assignment takes 282)
+    __builtin_amdgcn_s_setprio(3);
 #pragma unroll
     for (int i = 0; i < kRing - 1 && i < TOT; ++i) ring[i] = fetch(i);
 #pragma unroll
@@ -276,6 +279,7 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    __builtin_amdgcn_s_setprio(0);
   };
   constexpr std::true_type kYes{};
   constexpr std::false_type kNo{};
