@@ -26,7 +26,10 @@
  *     valid once the caller has synchronised that stream.  Calls that share a
  *     workspace must be ordered on one stream.
  *   - Every entry point returns a status (0 = OK, negative = error); nothing aborts,
- *     throws or prints.  On a non-zero status no kernel has been launched.
+ *     throws or prints.  Arguments and shapes are checked before anything is enqueued: on
+ *     INVALID_ARG, UNSUPPORTED_SHAPE and WORKSPACE_TOO_SMALL no kernel has been launched.
+ *     HIP_ERROR reports a failed runtime call; kernels of the same call launched before it
+ *     may already be enqueued, and the outputs are then undefined.
  *   - Readings of the paper where it is silent: softmax scale 1/sqrt(d_head) with d_head a
  *     free parameter; causal = key n visible to query m iff n <= m; RoPE = rotations of
  *     adjacent channel pairs (2j,2j+1) by angle position * base^(-2j/r3), applied as
@@ -69,6 +72,9 @@ typedef struct {
   int32_t dtype;          /* TUCKER_ATTN_F32 | TUCKER_ATTN_BF16: storage of X, weights, caches, Y; */
                           /* products accumulate in fp32 in both cases                             */
   int32_t max_positions;  /* rotation table covers positions 0 .. max_positions-1 (>= pos0+N, Lmax)*/
+                          /* The only size the context fixes: batch and sequence length are given  */
+                          /* per call and bound the workspace, which the caller sizes per call     */
+                          /* with tucker_attn_workspace_bytes(ctx, B, N).                          */
   int32_t shared_kv;      /* 0 | 1: shared key-value down-projection (Section "KV Caching"): the  */
                           /* value basis IS the key basis U3, so V = X U3 is the unrotated key     */
                           /* latent; needs rt3 == r3; weights.Ut3 is ignored (may be NULL); ONE    */
@@ -124,7 +130,8 @@ void tucker_attn_destroy(tucker_attn_ctx *ctx);
  * tokens (with save_for_backward: what tucker_attn_backward needs); 0 if an argument is invalid. */
 size_t tucker_attn_workspace_bytes(const tucker_attn_ctx *ctx, int32_t B, int32_t N);
 
-/* Bytes of device workspace tucker_attn_decode needs for B sequences; 0 if invalid. */
+/* Bytes of device workspace tucker_attn_decode needs for B sequences (it grows with B up to 32
+ * sequences, the size of one pass of the decode kernels, and stays there); 0 if invalid. */
 size_t tucker_attn_decode_workspace_bytes(const tucker_attn_ctx *ctx, int32_t B);
 
 /*
@@ -139,6 +146,8 @@ size_t tucker_attn_decode_workspace_bytes(const tucker_attn_ctx *ctx, int32_t B)
  *                NULL and Kcache_out, if given, receives the UNROTATED latent rows.
  *   workspace    device, >= tucker_attn_workspace_bytes(ctx,B,N) bytes, 256-byte aligned; scratch
  *   hip_stream   a hipStream_t (NULL = the null stream)
+ * Limits: B <= 65535 and B * roundup(N, 64) <= 65535 * 32 = 2 097 120 padded tokens (the launch grids),
+ * reported as TUCKER_ATTN_UNSUPPORTED_SHAPE before anything is enqueued.
  */
 int tucker_attn_forward(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
                         const void *X, void *Y, int32_t B, int32_t N, int32_t pos0,
@@ -155,8 +164,10 @@ int tucker_attn_forward(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
  *            rows (row kv_len[b]-1 is written unrotated).
  *   kv_len   HOST   [B] int32         cache length INCLUDING the new token, 1 <= kv_len[b] <= Lmax;
  *                                     the query sits at position kv_len[b]-1 and attends rows 0..kv_len[b]-1
- *   B        1 .. 32
+ *   B        >= 1; batches above 32 sequences run as consecutive passes of 32 on the stream
  * causal in the config is irrelevant here (the query is the last position).
+ * Limits (TUCKER_ATTN_UNSUPPORTED_SHAPE): n_heads <= 64; cache rows a multiple of 16 bytes; the attended
+ * part of one sequence's cache, kv_len[b] * max(r3, rt3) elements, below 2 GiB.
  */
 int tucker_attn_decode(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
                        const void *x, void *y, void *Kcache, void *Vcache, int32_t Lmax,
@@ -194,7 +205,7 @@ size_t tucker_attn_backward_workspace_bytes(const tucker_attn_ctx *ctx, int32_t 
  *                  with save_for_backward = 1) just used with the same w, X, B, N and pos0, and nothing
  *                  has written to it since: the forward is not run again.  INVALID_ARG if the context
  *                  was created without save_for_backward.
- * Same shape limits as forward, and B * roundup(N, 64) <= 2^21 tokens.
+ * Same shape limits as forward.
  */
 int tucker_attn_backward(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
                          const void *X, const void *dY, void *dX, const tucker_attn_grads *grads,

@@ -302,3 +302,15 @@ def relative_l2(a, b) -> float:
     """||a - b||_2 / ||b||_2 over all elements (b is the reference)."""
     a, b = _f64(a), _f64(b)
     return float(np.linalg.norm((a - b).ravel()) / np.linalg.norm(b.ravel()))
+
+
+def relative_l2_rows(a, b, floor=None):
+    """Per-row version of relative_l2: ||a[r] - b[r]||_2 / max(||b[r]||_2, floor) for every vector r
+    along the last axis.  `floor` (default: a hundredth of the root-mean-square row norm of b) keeps a
+    reference row that is zero or tiny from turning rounding noise into a large ratio."""
+    a, b = _f64(a), _f64(b)
+    num = np.linalg.norm(a - b, axis=-1)
+    den = np.linalg.norm(b, axis=-1)
+    if floor is None:
+        floor = 0.01 * math.sqrt(float(np.mean(den ** 2))) if den.size else 0.0
+    return num / np.maximum(np.maximum(den, floor), np.finfo(F64).tiny)

@@ -17,6 +17,10 @@ using namespace ta;
 namespace {
 constexpr int kMaxKernels = 40;
 constexpr size_t kAlign = 256;
+// Token tiles (32 padded tokens at the smallest) are the y dimension of the GEMM launches, which HIP
+// limits to 65535: more padded tokens than this are refused before anything is enqueued.
+constexpr long kMaxTokens = 65535l * 32;
+constexpr int kDecodeChunk = 32;      // sequences per pass of the decode kernels (their per-sequence arguments)
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 }  // namespace
 
@@ -322,6 +326,103 @@ int forward_core(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* X
   return TUCKER_ATTN_OK;
 }
 
+// One decode step of B sequences inside `workspace`.  The kernels take their per-sequence arguments
+// (cache length, position) by value for at most kDecodeChunk sequences, so a larger batch runs as
+// consecutive passes over chunks of sequences on the same stream, sharing the workspace; the weight
+// preparation runs once.
+int decode_impl(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x, void* y, void* Kcache, void* Vcache,
+                int32_t Lmax, const int32_t* kv_len, int32_t B, void* workspace, size_t workspace_bytes,
+                void* hip_stream) {
+  if (!c || !weights_ok(c, w) || !x || !y || !Kcache || !kv_len || !workspace) return TUCKER_ATTN_INVALID_ARG;
+  if (B < 1 || Lmax < 1) return TUCKER_ATTN_INVALID_ARG;
+  const tucker_attn_config& f = c->cfg;
+  if (f.shared_kv ? Vcache != nullptr : Vcache == nullptr) return TUCKER_ATTN_INVALID_ARG;
+  const long row_bytes = (long)(f.r3 > f.rt3 ? f.r3 : f.rt3) * c->es;
+  for (int b = 0; b < B; ++b) {
+    if (kv_len[b] < 1 || kv_len[b] > Lmax) return TUCKER_ATTN_INVALID_ARG;
+    if (f.use_rope && kv_len[b] > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
+    // the cache of one sequence is addressed through 32-bit byte offsets of a buffer descriptor
+    if ((long)kv_len[b] * row_bytes >= (1l << 31)) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  }
+  if (f.n_heads > 64) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  if ((f.r3 * c->es) % 16 != 0 || (f.rt3 * c->es) % 16 != 0) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
+  if (c->prepared && !same_weights(*w, c->prepared_from)) return TUCKER_ATTN_INVALID_ARG;
+  const int Bc_max = B < kDecodeChunk ? B : kDecodeChunk;
+  if (workspace_bytes < carve_decode(c, nullptr, Bc_max).bytes) return TUCKER_ATTN_WORKSPACE_TOO_SMALL;
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  Recorder rec{c, s, c->profile != 0};
+  if (rec.begin() != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+
+  for (int b0 = 0; b0 < B; b0 += kDecodeChunk) {
+    const int Bc = B - b0 < kDecodeChunk ? B - b0 : kDecodeChunk;
+    DecodeWs ws = carve_decode(c, workspace, Bc);                  // the weight copies come first: same place in every pass
+    use_prepared(c, ws);
+    const char* xb = static_cast<const char*>(x) + (size_t)b0 * f.d_model * c->es;
+    char* yb = static_cast<char*>(y) + (size_t)b0 * f.d_model * c->es;
+    char* Kb = static_cast<char*>(Kcache) + (size_t)b0 * Lmax * f.r3 * c->es;
+    char* Vb = Vcache ? static_cast<char*>(Vcache) + (size_t)b0 * Lmax * f.rt3 * c->es : nullptr;
+    const int32_t* len = kv_len + b0;
+
+    const void* ut2;
+    long ut2_ld;
+    PrepArgs pa = make_prep(c, w, ws.Gt, ws.Gtil2, ws.Wcat, ws.Ut2p, &ut2, &ut2_ld);
+    if (!c->prepared && b0 == 0) {
+      if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+      rec.after("prep_weights");
+    }
+
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A = ws.Wcat; g.lda = c->dp; g.M = c->R2 + (f.shared_kv ? 1 : 2) * c->D; g.shared_kv = f.shared_kv;
+    g.Bsrc = xb; g.ldb = f.d_model; g.K = f.d_model;
+    g.Bsz = Bc; g.N = 1; g.Npad = 1; g.src_padded = 0;
+    g.epi = 0;
+    g.Qlat = ws.Qlat; g.R2 = c->R2; g.Kr = nullptr; g.D = c->D; g.Vt = nullptr;
+    g.Kcache = Kb; g.Vcache = Vb; g.Lmax = Lmax; g.r3 = f.r3; g.rt3 = f.rt3;
+    g.rope = c->rope; g.rope_ld = f.max_positions; g.pos0 = 0; g.decode = 1;
+    for (int b = 0; b < Bc; ++b) g.kv_pos[b] = len[b] - 1;
+    g.ksplit = decode_ksplit(g.K); g.part = ws.part;
+    if (launch_gemm(f.dtype, g, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("factor_projection");
+
+    DecodeArgs d;
+    std::memset(&d, 0, sizeof(d));
+    d.Qlat = ws.Qlat; d.Gt = ws.Gt; d.Qh = ws.Qh; d.Kcache = Kb; d.Vcache = Vb;
+    d.part_m = ws.pm; d.part_l = ws.pl; d.part_o = ws.po; d.O = ws.O; d.rope = c->rope; d.rope_ld = f.max_positions;
+    d.Bsz = Bc; d.nH = f.n_heads; d.HB = pad32(f.n_heads) / 32; d.R2 = c->R2; d.r3 = f.r3; d.rt3 = f.rt3;
+    d.D = c->D; d.Lmax = Lmax; d.nsplit = decode_nsplit(Bc); d.shared_kv = f.shared_kv;
+    for (int b = 0; b < Bc; ++b) d.kv_len[b] = len[b];
+    if (launch_decode_qhat(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("decode_query");
+    if (launch_decode_attn(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("decode_attention");
+    if (launch_decode_merge(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("decode_merge");
+
+    GemmArgs z;
+    std::memset(&z, 0, sizeof(z));
+    z.A = ws.Gtil2; z.lda = (long)f.n_heads * c->D; z.M = c->RT2;
+    z.Bsrc = ws.O; z.ldb = (long)f.n_heads * c->D; z.K = f.n_heads * c->D;
+    z.Bsz = Bc; z.N = 1; z.Npad = 1; z.src_padded = 1;
+    z.epi = 1; z.Out = ws.Z; z.ldo = c->RT2;
+    z.ksplit = decode_ksplit(z.K); z.part = ws.part;
+    if (launch_gemm(f.dtype, z, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("latent_merge");
+
+    GemmArgs yy;
+    std::memset(&yy, 0, sizeof(yy));
+    yy.A = ut2; yy.lda = ut2_ld; yy.M = f.d_model;
+    yy.Bsrc = ws.Z; yy.ldb = c->RT2; yy.K = c->RT2;
+    yy.Bsz = Bc; yy.N = 1; yy.Npad = 1; yy.src_padded = 1;
+    yy.epi = 2; yy.Out = yb; yy.ldo = f.d_model; yy.ksplit = 1;
+    if (launch_gemm(f.dtype, yy, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    rec.after("output_projection");
+  }
+  return TUCKER_ATTN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -417,8 +518,8 @@ size_t tucker_attn_workspace_bytes(const tucker_attn_ctx* c, int32_t B, int32_t 
 }
 
 size_t tucker_attn_decode_workspace_bytes(const tucker_attn_ctx* c, int32_t B) {
-  if (!c || B < 1 || B > 32) return 0;
-  return carve_decode(c, nullptr, B).bytes;
+  if (!c || B < 1) return 0;
+  return carve_decode(c, nullptr, B < kDecodeChunk ? B : kDecodeChunk).bytes;
 }
 
 int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* X, void* Y, int32_t B,
@@ -431,7 +532,7 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
     return TUCKER_ATTN_INVALID_ARG;
   if (Kcache_out && (Lmax < 1 || (long)pos0 + N > Lmax)) return TUCKER_ATTN_INVALID_ARG;
   if (f.use_rope && (long)pos0 + N > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
-  if ((long)B * pad64(N) > (1l << 30) / 64 || B > 65535) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  if ((long)B * pad64(N) > kMaxTokens || B > 65535) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
   if (c->prepared && !same_weights(*w, c->prepared_from)) return TUCKER_ATTN_INVALID_ARG;
   PrefillWs ws = carve_prefill(c, workspace, B, N);
@@ -440,7 +541,6 @@ int tucker_attn_forward(tucker_attn_ctx* c, const tucker_attn_weights* w, const 
   float* lse = nullptr;
   size_t need = ws.bytes;
   if (f.save_for_backward) {                                    // the backward layout, of which ws is the head
-    if ((long)B * pad64(N) > (1l << 21)) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
     const BackwardWs bw = carve_backward(c, workspace, B, N);
     Vr = bw.Vr; Krt = bw.Krt; lse = bw.lse; need = bw.bytes;
   }
@@ -487,7 +587,7 @@ int tucker_attn_backward(tucker_attn_ctx* c, const tucker_attn_weights* w, const
   if (forward_state != 0 && forward_state != 1) return TUCKER_ATTN_INVALID_ARG;
   if (forward_state && !f.save_for_backward) return TUCKER_ATTN_INVALID_ARG;
   if (f.use_rope && (long)pos0 + N > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
-  if ((long)B * pad64(N) > (1l << 21) || B > 65535) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
+  if ((long)B * pad64(N) > kMaxTokens || B > 65535) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
   if (c->prepared && !same_weights(*w, c->prepared_from)) return TUCKER_ATTN_INVALID_ARG;
   BackwardWs ws = carve_backward(c, workspace, B, N);
@@ -649,81 +749,8 @@ int tucker_attn_backward(tucker_attn_ctx* c, const tucker_attn_weights* w, const
 int tucker_attn_decode(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x, void* y, void* Kcache,
                        void* Vcache, int32_t Lmax, const int32_t* kv_len, int32_t B, void* workspace,
                        size_t workspace_bytes, void* hip_stream) {
-  if (!c || !weights_ok(c, w) || !x || !y || !Kcache || !kv_len || !workspace) return TUCKER_ATTN_INVALID_ARG;
-  if (B < 1 || B > 32 || Lmax < 1) return TUCKER_ATTN_INVALID_ARG;
-  const tucker_attn_config& f = c->cfg;
-  if (f.shared_kv ? Vcache != nullptr : Vcache == nullptr) return TUCKER_ATTN_INVALID_ARG;
-  for (int b = 0; b < B; ++b) {
-    if (kv_len[b] < 1 || kv_len[b] > Lmax) return TUCKER_ATTN_INVALID_ARG;
-    if (f.use_rope && kv_len[b] > f.max_positions) return TUCKER_ATTN_INVALID_ARG;
-  }
-  if (f.n_heads > 64) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
-  if ((f.r3 * c->es) % 16 != 0 || (f.rt3 * c->es) % 16 != 0) return TUCKER_ATTN_UNSUPPORTED_SHAPE;
-  if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return TUCKER_ATTN_INVALID_ARG;
-  if (c->prepared && !same_weights(*w, c->prepared_from)) return TUCKER_ATTN_INVALID_ARG;
-  DecodeWs ws = carve_decode(c, workspace, B);
-  use_prepared(c, ws);
-  if (workspace_bytes < ws.bytes) return TUCKER_ATTN_WORKSPACE_TOO_SMALL;
-
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  Recorder rec{c, s, c->profile != 0};
-  if (rec.begin() != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-
-  const void* ut2;
-  long ut2_ld;
-  PrepArgs pa = make_prep(c, w, ws.Gt, ws.Gtil2, ws.Wcat, ws.Ut2p, &ut2, &ut2_ld);
-  if (!c->prepared) {
-    if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-    rec.after("prep_weights");
-  }
-
-  GemmArgs g;
-  std::memset(&g, 0, sizeof(g));
-  g.A = ws.Wcat; g.lda = c->dp; g.M = c->R2 + (f.shared_kv ? 1 : 2) * c->D; g.shared_kv = f.shared_kv;
-  g.Bsrc = x; g.ldb = f.d_model; g.K = f.d_model;
-  g.Bsz = B; g.N = 1; g.Npad = 1; g.src_padded = 0;
-  g.epi = 0;
-  g.Qlat = ws.Qlat; g.R2 = c->R2; g.Kr = nullptr; g.D = c->D; g.Vt = nullptr;
-  g.Kcache = Kcache; g.Vcache = Vcache; g.Lmax = Lmax; g.r3 = f.r3; g.rt3 = f.rt3;
-  g.rope = c->rope; g.rope_ld = f.max_positions; g.pos0 = 0; g.decode = 1;
-  for (int b = 0; b < B; ++b) g.kv_pos[b] = kv_len[b] - 1;
-  g.ksplit = decode_ksplit(g.K); g.part = ws.part;
-  if (launch_gemm(f.dtype, g, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("factor_projection");
-
-  DecodeArgs d;
-  std::memset(&d, 0, sizeof(d));
-  d.Qlat = ws.Qlat; d.Gt = ws.Gt; d.Qh = ws.Qh; d.Kcache = Kcache; d.Vcache = Vcache;
-  d.part_m = ws.pm; d.part_l = ws.pl; d.part_o = ws.po; d.O = ws.O; d.rope = c->rope; d.rope_ld = f.max_positions;
-  d.Bsz = B; d.nH = f.n_heads; d.HB = pad32(f.n_heads) / 32; d.R2 = c->R2; d.r3 = f.r3; d.rt3 = f.rt3;
-  d.D = c->D; d.Lmax = Lmax; d.nsplit = decode_nsplit(B); d.shared_kv = f.shared_kv;
-  for (int b = 0; b < B; ++b) d.kv_len[b] = kv_len[b];
-  if (launch_decode_qhat(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("decode_query");
-  if (launch_decode_attn(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("decode_attention");
-  if (launch_decode_merge(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("decode_merge");
-
-  GemmArgs z;
-  std::memset(&z, 0, sizeof(z));
-  z.A = ws.Gtil2; z.lda = (long)f.n_heads * c->D; z.M = c->RT2;
-  z.Bsrc = ws.O; z.ldb = (long)f.n_heads * c->D; z.K = f.n_heads * c->D;
-  z.Bsz = B; z.N = 1; z.Npad = 1; z.src_padded = 1;
-  z.epi = 1; z.Out = ws.Z; z.ldo = c->RT2;
-  z.ksplit = decode_ksplit(z.K); z.part = ws.part;
-  if (launch_gemm(f.dtype, z, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("latent_merge");
-
-  GemmArgs yy;
-  std::memset(&yy, 0, sizeof(yy));
-  yy.A = ut2; yy.lda = ut2_ld; yy.M = f.d_model;
-  yy.Bsrc = ws.Z; yy.ldb = c->RT2; yy.K = c->RT2;
-  yy.Bsz = B; yy.N = 1; yy.Npad = 1; yy.src_padded = 1;
-  yy.epi = 2; yy.Out = y; yy.ldo = f.d_model; yy.ksplit = 1;
-  if (launch_gemm(f.dtype, yy, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-  rec.after("output_projection");
-  return TUCKER_ATTN_OK;
+  if (!workspace) return TUCKER_ATTN_INVALID_ARG;
+  return decode_impl(c, w, x, y, Kcache, Vcache, Lmax, kv_len, B, workspace, workspace_bytes, hip_stream);
 }
 
 size_t tucker_attn_prepared_weights_bytes(const tucker_attn_ctx* c) { return c ? prepared_bytes(c) : 0; }

@@ -87,8 +87,10 @@ def test_workspace_sizes_and_host_side_argument_checks():
         small, big = ta.tucker_attn_workspace_bytes(ctx, 1, 64), ta.tucker_attn_workspace_bytes(ctx, 2, 128)
         assert 0 < small < big and small % 256 == 0
         assert ta.tucker_attn_workspace_bytes(ctx, 1, 1) == small          # tokens are padded to 64
-        assert ta.tucker_attn_decode_workspace_bytes(ctx, 33) == 0
-        assert ta.tucker_attn_decode_workspace_bytes(ctx, 4) > 0
+        assert ta.tucker_attn_decode_workspace_bytes(ctx, 0) == 0
+        assert 0 < ta.tucker_attn_decode_workspace_bytes(ctx, 4) <= ta.tucker_attn_decode_workspace_bytes(ctx, 32)
+        # batches above 32 sequences run in passes of 32 that share the workspace
+        assert ta.tucker_attn_decode_workspace_bytes(ctx, 1000) == ta.tucker_attn_decode_workspace_bytes(ctx, 32)
         lib = ta.load_library()
         w = ta.tucker_attn_weights(*([1] * 8))
         # null X / Y / workspace, bad sizes: rejected on the host before any launch
@@ -104,6 +106,14 @@ def test_workspace_sizes_and_host_side_argument_checks():
         assert lib.tucker_attn_decode(ctx, C.byref(w), 256, 256, 256, 256, 8, lens, 2, 256, 1 << 30, None) == -1
         lens = (C.c_int32 * 2)(5, 8)
         assert lib.tucker_attn_decode(ctx, C.byref(w), 256, 256, 256, 256, 8, lens, 2, 256, 16, None) == -3
+        # more padded tokens than the launch grids can index: refused before anything is enqueued
+        assert lib.tucker_attn_forward(ctx, C.byref(w), 256, 256, 1, 65535 * 32 + 1, 0, None, None, 0, 256, 1 << 60, None) == -2
+        assert lib.tucker_attn_forward(ctx, C.byref(w), 256, 256, 70000, 16, 0, None, None, 0, 256, 1 << 60, None) == -2
+        # the attended part of one sequence's cache must stay below 2 GiB (r3 = 32 fp32 channels = 128 bytes per row)
+        lens = (C.c_int32 * 1)(1 << 24)
+        assert lib.tucker_attn_decode(ctx, C.byref(w), 256, 256, 256, 256, 1 << 24, lens, 1, 256, 1 << 30, None) == -2
+        lens = (C.c_int32 * 1)((1 << 24) - 1)
+        assert lib.tucker_attn_decode(ctx, C.byref(w), 256, 256, 256, 256, 1 << 24, lens, 1, 256, 16, None) == -3
     finally:
         ta.tucker_attn_destroy(ctx)
 
