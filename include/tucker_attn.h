@@ -174,6 +174,23 @@ int tucker_attn_decode(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
                        const int32_t *kv_len, int32_t B,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * tucker_attn_decode for callers that cannot allocate device memory or keep a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels
+ * and results as tucker_attn_decode, without the workspace: the scratch memory is a 32 MiB
+ * (33 554 432 bytes) device array that is part of the loaded library (each GPU the library runs on
+ * holds its own copy until the process ends).  The call allocates and frees nothing.
+ *   - TUCKER_ATTN_WORKSPACE_TOO_SMALL if tucker_attn_decode_workspace_bytes(ctx, B) exceeds 32 MiB
+ *     (the LLaMA-7B layer shape with ranks [8,128,128] needs about 15 MiB at any B); nothing is enqueued.
+ *   - Every call on a GPU, from any context, uses that GPU's one array: calls must be ordered on one
+ *     stream or otherwise synchronised; calls that overlap on one GPU race.  The array keeps the last
+ *     call's contents; no part of it has to start at zero (every piece is written before it is read
+ *     within a call), so nothing is cleared.
+ */
+int tucker_attn_decode_static(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
+                              const void *x, void *y, void *Kcache, void *Vcache, int32_t Lmax,
+                              const int32_t *kv_len, int32_t B, void *hip_stream);
+
 /* Device pointers that receive the weight gradients, fp32 whatever the storage type (they are
  * sums over all tokens); caller-owned, overwritten (not accumulated into). */
 typedef struct {

@@ -19,7 +19,7 @@ TUCKER_ATTN_BF16 = 1
 EXPORTED = [
     "tucker_attn_create", "tucker_attn_destroy", "tucker_attn_parameter_count", "tucker_attn_cache_bytes",
     "tucker_attn_workspace_bytes",
-    "tucker_attn_decode_workspace_bytes", "tucker_attn_forward", "tucker_attn_decode",
+    "tucker_attn_decode_workspace_bytes", "tucker_attn_forward", "tucker_attn_decode", "tucker_attn_decode_static",
     "tucker_attn_backward_workspace_bytes", "tucker_attn_backward",
     "tucker_attn_prepared_weights_bytes", "tucker_attn_prepare_weights", "tucker_attn_release_weights",
     "tucker_attn_profile_enable", "tucker_attn_profile_read", "tucker_attn_status_string",
@@ -100,6 +100,10 @@ def load_library() -> C.CDLL:
                                        C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32,
                                        C.c_void_p, C.c_size_t, C.c_void_p]
     lib.tucker_attn_decode.restype = C.c_int
+    lib.tucker_attn_decode_static.argtypes = [ctx_p, C.POINTER(tucker_attn_weights), C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.c_int32,
+                                              C.c_void_p]
+    lib.tucker_attn_decode_static.restype = C.c_int
     lib.tucker_attn_backward_workspace_bytes.argtypes = [ctx_p, C.c_int32, C.c_int32]
     lib.tucker_attn_backward_workspace_bytes.restype = C.c_size_t
     lib.tucker_attn_backward.argtypes = [ctx_p, C.POINTER(tucker_attn_weights), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -221,6 +225,20 @@ def tucker_attn_decode(ctx: int, weights: Dict, x, y, Kcache, Vcache, kv_len: Li
                                            _stream_ptr(stream))
     if check:
         _check(st, "tucker_attn_decode")
+    return st
+
+
+def tucker_attn_decode_static(ctx: int, weights: Dict, x, y, Kcache, Vcache, kv_len: List[int], stream=None,
+                              check: bool = True) -> int:
+    """tucker_attn_decode on the library's own static scratch array (no workspace, no allocation)."""
+    B = int(x.shape[0])
+    Lmax = int(Kcache.shape[1])
+    lens = (C.c_int32 * B)(*[int(v) for v in kv_len])
+    ws = _weights_struct(weights)
+    st = load_library().tucker_attn_decode_static(ctx, C.byref(ws), x.data_ptr(), y.data_ptr(), Kcache.data_ptr(),
+                                                  _ptr(Vcache), Lmax, lens, B, _stream_ptr(stream))
+    if check:
+        _check(st, "tucker_attn_decode_static")
     return st
 
 

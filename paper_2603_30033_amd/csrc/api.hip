@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -24,6 +25,12 @@ constexpr int kDecodeChunk = 32;      // sequences per pass of the decode kernel
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 }  // namespace
 
+// Workspace of tucker_attn_decode_static: device memory that belongs to the loaded library, one copy on
+// every GPU the library runs on, held until the process ends.  In host code the name is only a handle
+// for hipGetSymbolAddress; the address kernels and copies use is the one static_scratch() returns.
+constexpr size_t kStaticScratchBytes = 32ul << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 struct tucker_attn_ctx {
   tucker_attn_config cfg;
   int R2, RT2, D, dp;          // padded ranks, common K/V width, padded d
@@ -42,6 +49,26 @@ struct tucker_attn_ctx {
 };
 
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+hipError_t static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> ptrs[kMaxDevices];
+  *out = nullptr;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* p = ptrs[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    ptrs[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return hipSuccess;
+}
 
 struct Carver {
   char* base;
@@ -485,6 +512,10 @@ int tucker_attn_create(const tucker_attn_config* cfg, tucker_attn_ctx** out) {
       return TUCKER_ATTN_HIP_ERROR;
     }
   }
+  if (f.use_rope) {                                             // a device is current (the table was just copied to it):
+    void* unused;                                               // look up this device's static scratch now rather than
+    (void)static_scratch(&unused);                              // on the first tucker_attn_decode_static call
+  }
   *out = c;
   return TUCKER_ATTN_OK;
 }
@@ -751,6 +782,16 @@ int tucker_attn_decode(tucker_attn_ctx* c, const tucker_attn_weights* w, const v
                        size_t workspace_bytes, void* hip_stream) {
   if (!workspace) return TUCKER_ATTN_INVALID_ARG;
   return decode_impl(c, w, x, y, Kcache, Vcache, Lmax, kv_len, B, workspace, workspace_bytes, hip_stream);
+}
+
+int tucker_attn_decode_static(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x, void* y, void* Kcache,
+                              void* Vcache, int32_t Lmax, const int32_t* kv_len, int32_t B, void* hip_stream) {
+  if (!c || B < 1) return TUCKER_ATTN_INVALID_ARG;
+  if (carve_decode(c, nullptr, B < kDecodeChunk ? B : kDecodeChunk).bytes > kStaticScratchBytes)
+    return TUCKER_ATTN_WORKSPACE_TOO_SMALL;
+  void* ws = nullptr;
+  if (static_scratch(&ws) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+  return decode_impl(c, w, x, y, Kcache, Vcache, Lmax, kv_len, B, ws, kStaticScratchBytes, hip_stream);
 }
 
 size_t tucker_attn_prepared_weights_bytes(const tucker_attn_ctx* c) { return c ? prepared_bytes(c) : 0; }
