@@ -18,19 +18,85 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+# MI355X published dense peaks.  The bf16 figure is the rounded 2.5 PFLOP/s; at 256 compute units x 4096
+# FLOP/clock x 2.4 GHz it is 2516.6, so fractions quoted here are 0.7 % (relative) above that basis.
+PEAK_BF16_TFLOPS = 2500.0
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel (read + written), from the rocprofv3 FETCH_SIZE and
-# WRITE_SIZE runs summarised in profiles/hbm_traffic_<workload>.md, scaled by what the same counters
-# read for a plain 256 MiB copy (factors 1.9998 and 1.0000).  Workloads without a counter run report null.
-MEASURED_TRAFFIC_BYTES = {
-    ("llama7b_n4096", "attention"): 132690388,
-    ("decode_32k", "decode_attention"): 278178687,
-    ("llama7b_n4096", "attention_bwd_dq+attention_bwd_dkv"): 955861929,
-    ("llama7b_n4096", "jacobi_block_kernel"): 309868665,
-}
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def library_build_id():
+    """Hash of the kernel sources the loaded library was built from (the library is built in-tree from
+    exactly these files), so that figures measured with one build are not reported for another."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2603_30033_amd", "csrc")
+    h = hashlib.sha1()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` (read + written) from the hardware-counter runs recorded in
+    profiles/hbm_traffic.json (written by `bench.py --pmc-summary`), or None if there is no record for this
+    workload and kernel made with the library build that is loaded now."""
+    try:
+        rec = json.load(open(TRAFFIC_JSON))
+    except (OSError, ValueError):
+        return None
+    e = rec.get(f"{workload}:{kernel}")
+    if not e or e.get("build_id") != library_build_id():
+        return None
+    return e.get("bytes")
+
+
+def pmc_summary(args):
+    """Turn two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB per dispatch) of `bench.py --workload W
+    --copy-calibration-mib M` into HBM bytes per launch of the kernels named by --pmc-kernels, scaled by what
+    the same counters read for the plain copy of known size, and record them in profiles/hbm_traffic.json."""
+    import csv
+    import glob
+
+    def per_kernel(root, counter):
+        tot, cnt = {}, {}
+        for f in glob.glob(os.path.join(root, "**", "*counter_collection.csv"), recursive=True):
+            for row in csv.DictReader(open(f)):
+                if row.get("Counter_Name") != counter:
+                    continue
+                k = row["Kernel_Name"]
+                tot[k] = tot.get(k, 0.0) + float(row["Counter_Value"])
+                cnt[k] = cnt.get(k, 0) + 1
+        return {k: tot[k] / cnt[k] for k in tot}, cnt
+
+    fetch, nf = per_kernel(args.pmc_summary[0], "FETCH_SIZE")
+    write, nw = per_kernel(args.pmc_summary[1], "WRITE_SIZE")
+    copy_bytes = args.copy_calibration_mib << 20
+    ck = [k for k in fetch if "copy" in k.lower() or "elementwise" in k.lower()]
+    assert ck and copy_bytes > 0, "the counter runs must include the calibration copy (--copy-calibration-mib)"
+    ck = max(ck, key=lambda k: fetch[k])
+    f_scale, w_scale = copy_bytes / (fetch[ck] * 1024.0), copy_bytes / (write[ck] * 1024.0)
+    try:
+        rec = json.load(open(TRAFFIC_JSON))
+    except (OSError, ValueError):
+        rec = {}
+    for spec in args.pmc_kernels:
+        label, pattern = spec.split("=", 1)
+        pats = pattern.split("+")
+        fk = [k for k in fetch if any(p in k for p in pats)]
+        assert fk, f"no kernel matches {pattern}"
+        rd = sum(fetch[k] for k in fk) * 1024.0 * f_scale
+        wr = sum(write.get(k, 0.0) for k in fk) * 1024.0 * w_scale
+        rec[f"{args.workload}:{label}"] = {
+            "bytes": int(rd + wr), "read_bytes": int(rd), "written_bytes": int(wr), "dispatches": int(nf[fk[0]]),
+            "fetch_scale": round(f_scale, 4), "write_scale": round(w_scale, 4), "build_id": library_build_id(),
+            "kernels": sorted(fk)}
+        log(f"{args.workload}:{label}: read {rd / 2**20:.1f} MiB, written {wr / 2**20:.1f} MiB per launch "
+            f"(scales {f_scale:.4f}, {w_scale:.4f})")
+    json.dump(rec, open(TRAFFIC_JSON, "w"), indent=1, sort_keys=True)
 
 
 def log(*a):
@@ -126,8 +192,9 @@ def cpu_baseline(w, backward=False):
         f = flops(ws)["total"]
         sample = f"full oracle forward of {b} sequence(s) of {n} tokens of the same layer shape"
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    return {"value": f / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": sample, "seconds": round(dt, 3)}
+    # cores = threads of the BLAS pool the oracle's matrix products ran on; host_cpus = what the box reports
+    return {"value": f / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "cores_kind": "BLAS threads",
+            "host_cpus": os.cpu_count(), "kind": "oracle", "sample": sample, "seconds": round(dt, 3)}
 
 
 def bench_convert_hosvd(w, args):
@@ -174,7 +241,7 @@ def bench_convert_hosvd(w, args):
         "pass": "convert_hosvd", "sweeps": infos[-1]["sweeps"],
         "roofline": {"kernel": "jacobi_block_kernel", "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS,
                      "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "jacobi_block_kernel")),
+                     "traffic": measured_traffic(w.name, "jacobi_block_kernel"),
                      "algorithmic_bytes": jac_bytes / max(launches, 1), "avg_us": jac_ms * 1e3 / max(launches, 1),
                      "launches": launches},
     }
@@ -193,7 +260,8 @@ def bench_convert_hosvd(w, args):
         cv.mha_to_tucker_hosvd(sample["WQ"], sample["WK"], sample["WV"], sample["WO"], hs, rs, rts, shared_kv=w.shared_kv)
         cpu = time.perf_counter() - t0
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        out["cpu_baseline"] = {"value": cpu, "unit": "s", "cores": int(threads), "kind": "oracle",
+        out["cpu_baseline"] = {"value": cpu, "unit": "s", "cores": int(threads), "cores_kind": "BLAS threads",
+                               "host_cpus": os.cpu_count(), "kind": "oracle",
                                "sample": f"oracle conversion of a layer with d={ds}, {hs} heads of width {dH} "
                                          f"(dense tensors, LAPACK SVD of the three unfoldings)"}
     return out
@@ -223,6 +291,11 @@ def main():
                     help="capture the launches of one step into a HIP graph once and time replays of it (the library "
                          "only enqueues kernels on the caller's stream, so a step can be captured as it is)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-summary", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
+                    help="no GPU work: read the counter CSVs of two rocprofv3 --pmc runs of this script (FETCH_SIZE, "
+                         "WRITE_SIZE) and record HBM bytes per launch in profiles/hbm_traffic.json")
+    ap.add_argument("--pmc-kernels", nargs="*", default=[],
+                    help="with --pmc-summary: label=substring[+substring] of the kernel names to record")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also launch a plain device-to-device copy of this many MiB (three times), so that a "
                          "hardware-counter run holds a kernel of known HBM traffic to scale its readings by")
@@ -231,6 +304,10 @@ def main():
         log("bench.py measures the one-GPU hot path only; run it with --gpus 1 "
             "(batch, head and sequence sharding are described in the repository's design notes)")
         sys.exit(2)
+
+    if args.pmc_summary:
+        pmc_summary(args)
+        return
 
     import numpy as np
     import torch
@@ -316,16 +393,48 @@ def main():
 
         timed_step = step
         if args.hip_graph:
-            step()                                              # first call outside the capture
+            # one captured step per cache buffer, replayed in rotation (a decode step keeps streaming its cache
+            # from HBM; a prefill workload has one buffer set, i.e. one graph)
+            n_graphs = 3 if w.mode == "decode" else 1
+            for _ in range(n_graphs):
+                step()                                          # first calls outside the capture
             torch.cuda.synchronize()
-            graph = torch.cuda.CUDAGraph()
+            graphs = []
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
             with torch.cuda.stream(side):
-                with torch.cuda.graph(graph, stream=side):
-                    step()
+                for _ in range(n_graphs):
+                    gr = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(gr, stream=side):
+                        step()
+                    graphs.append(gr)
             torch.cuda.current_stream().wait_stream(side)
-            timed_step = graph.replay
+            replay_i = [0]
+
+            def timed_step():
+                graphs[replay_i[0] % n_graphs].replay()
+                replay_i[0] += 1
+
+        def event_times(n):
+            """n steps, each between its own pair of HIP events on the stream the library launches on."""
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+            for a, b in ev:
+                a.record()
+                timed_step()
+                b.record()
+            torch.cuda.synchronize()
+            return [a.elapsed_time(b) for a, b in ev]
+
+        # Clock warm-up (untimed, before --warmup): the first launches after idle run at a lower shader clock.
+        # Blocks of 10 steps are run until the median of a block is within 1 % of the previous block's, at most
+        # 40 blocks.
+        clock_steps, prev = 0, None
+        for _ in range(40):
+            cur = float(np.median(event_times(10)))
+            clock_steps += 10
+            if prev is not None and abs(cur - prev) <= 0.01 * prev:
+                break
+            prev = cur
         for _ in range(W):
             timed_step()
         torch.cuda.synchronize()
@@ -335,6 +444,9 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         ms = dt / K * 1e3
+        # the same K steps once more, each timed by its own event pair: median and minimum
+        per_step = event_times(K)
+        median_ms, min_ms = float(np.median(per_step)), float(np.min(per_step))
 
         # per-kernel durations: the same K steps again with HIP events around every launch
         ta.tucker_attn_profile_enable(layer.ctx, True)
@@ -352,7 +464,8 @@ def main():
 
     total_flops = fb["total"] if backward else fl["total"]
     tflops = total_flops / (ms * 1e-3) / 1e12
-    log(f"{w.name}: {ms:.4f} ms/step, {tflops:.1f} TFLOP/s algorithmic, {units / (ms * 1e-3):.3e} tokens/s")
+    log(f"{w.name}: {ms:.4f} ms/step (events: median {median_ms:.4f}, min {min_ms:.4f}; {clock_steps} clock warm-up "
+        f"steps), {tflops:.1f} TFLOP/s algorithmic, {units / (ms * 1e-3):.3e} tokens/s")
     for n in order:
         log(f"  {n:20s} {kern_ms[n] * 1e3:9.1f} us")
     log(f"  sum of kernels       {sum(kern_ms.values()) * 1e3:9.1f} us")
@@ -365,7 +478,7 @@ def main():
         alg = fb["attn"] + 2 * fl["qhat"]
         ach = alg / (t_ms * 1e-3) / 1e12
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                "frac": ach / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)), "algorithmic_flops": alg,
+                "frac": ach / peak, "traffic": measured_traffic(w.name, dom), "algorithmic_flops": alg,
                 "avg_us": t_ms * 1e3}
     elif w.mode == "decode":
         dom = "decode_attention"
@@ -374,20 +487,24 @@ def main():
         alg_bytes = w.B * w.kv_len * (w.r3 + (0 if w.shared_kv else rt3)) * es
         ach = alg_bytes / (kern_ms[dom] * 1e-3) / 1e9
         roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                "frac": ach / PEAK_HBM_GBS, "traffic": measured_traffic(w.name, dom),
                 "algorithmic_bytes": alg_bytes, "avg_us": kern_ms[dom] * 1e3}
     else:
         dom = "attention"
         peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_MFMA_TFLOPS
         ach = (fl["attn"] + fl["qhat"]) / (kern_ms[dom] * 1e-3) / 1e12
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                "frac": ach / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                "frac": ach / peak, "traffic": measured_traffic(w.name, dom),
                 "algorithmic_flops": fl["attn"] + fl["qhat"], "avg_us": kern_ms[dom] * 1e3}
 
     out = {
         "metric": ("tucker_attn_bwd_tflops" if backward else
                    "tucker_attn_fwd_tflops" if w.mode != "decode" else "tucker_attn_decode_tflops"),
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms,
+        "median_ms": median_ms, "min_ms": min_ms, "clock_warmup_steps": clock_steps,
+        "timing": "value and ms_per_step: wall clock around the K steps, device synchronised on both sides; "
+                  "median_ms and min_ms: one HIP event pair per step on the launch stream, K further steps; "
+                  "clock_warmup_steps untimed steps ran first, until the step time settled",
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "N": w.N if w.mode != "decode" else w.kv_len,
                    "d_model": w.d_model, "n_heads": w.n_heads, "d_head": w.d_head,
@@ -399,6 +516,8 @@ def main():
         "hbm_gbs_mandatory": mandatory_bytes(w) / (ms * 1e-3) / 1e9,
         "algorithmic_gflop": total_flops / 1e9,
         "kernel_us": {n: kern_ms[n] * 1e3 for n in order},
+        "peak_basis": "published dense peaks: bf16 MFMA 2500 TFLOP/s (2516.6 at 2.4 GHz), HBM 8000 GB/s",
+        "library_build_id": library_build_id(),
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

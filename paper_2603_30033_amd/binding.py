@@ -11,7 +11,8 @@ import os
 from typing import Dict, List, Optional, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtucker_attn.so")
+# TUCKER_ATTN_LIB names another build of the same library (comparing two builds in one session)
+LIB_PATH = os.environ.get("TUCKER_ATTN_LIB") or os.path.join(_HERE, "libtucker_attn.so")
 
 TUCKER_ATTN_F32 = 0
 TUCKER_ATTN_BF16 = 1
