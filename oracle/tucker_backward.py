@@ -51,11 +51,12 @@ def _unrotate(x: np.ndarray, positions: np.ndarray, base: Optional[float]) -> np
 
 def backward(X, dY, wts: Dict[str, np.ndarray], d_head: int, causal: bool,
              rope_base: Optional[float] = None, pos0: int = 0,
-             shared_kv: bool = False) -> Dict[str, np.ndarray]:
+             shared_kv: bool = False, return_mixed: bool = False) -> Dict[str, np.ndarray]:
     """Gradients of sum(dY * Y) for X [B,N,d] and every weight array.
 
     Returns a dict with keys dX, dC, dU1, dU2, dU3, dCt, dUt1, dUt2 and, unless the latent is
-    shared, dUt3.  All fp64.
+    shared, dUt3.  All fp64.  return_mixed adds dG and dGt, the gradients of the head-mixed cores
+    G_i = sum_a U1[i,a] C[a] and G~_i, from which dC, dU1, dCt, dUt1 are contracted.
     """
     X, dY = _f64(X), _f64(dY)
     B, N, d = X.shape
@@ -136,4 +137,16 @@ def backward(X, dY, wts: Dict[str, np.ndarray], d_head: int, causal: bool,
     }
     if not shared_kv:
         out["dUt3"] = dUt3
+    if return_mixed:
+        out["dG"], out["dGt"] = dG, dGt
     return out
+
+
+def head_factor_cancellation(dG, C) -> float:
+    """How much the head-factor gradient dU1[i,a] = sum_bc dG[i,b,c] C[a,b,c] cancels: the norm of the sums
+    of absolute terms over the norm of the sums themselves (1 = no cancellation).  A relative perturbation
+    eps of the terms moves the result by up to eps times this factor, relative to its own size."""
+    dG, C = _f64(dG), _f64(C)
+    val = np.einsum("ibc,abc->ia", dG, C)
+    mag = np.einsum("ibc,abc->ia", np.abs(dG), np.abs(C))
+    return float(np.linalg.norm(mag) / np.linalg.norm(val))

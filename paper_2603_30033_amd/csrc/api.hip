@@ -239,7 +239,7 @@ void add_job(PrepArgs& pa, const void* src, const void* coef, void* out, int A, 
   j.out_stride_z = sz; j.out_stride_u = su;
   j.transposed = transposed; j.perm = perm; j.scale = scale; j.frag = frag;
   j.first_block = pa.total_blocks;
-  pa.total_blocks += Z * (rows_pad / 32) * (cols_pad / 32);
+  pa.total_blocks += prep_job_blocks(j);
 }
 
 // head-mixed cores and factor matrices in MFMA operand layout; returns the output-factor pointer

@@ -25,7 +25,7 @@ struct PrepJob {
   long out_stride_z, out_stride_u;
   int transposed, perm, frag;
   float scale;
-  int first_block;      // prefix sum of tile counts
+  int first_block;      // prefix sum of the jobs' workgroup counts (prep_job_blocks)
 };
 constexpr int kMaxPrepJobs = 8;
 struct PrepArgs {
@@ -181,6 +181,7 @@ inline hipError_t allow_dynamic_lds(LdsOnce& once, K kernel, size_t bytes) {
   return e;
 }
 
+int prep_job_blocks(const PrepJob& j);     // workgroups (output tiles) of one job
 hipError_t launch_prep(int dtype, const PrepArgs& a, hipStream_t s);
 bool out_proj_supported(int dtype, const GemmArgs& a);
 hipError_t launch_out_proj(int dtype, const GemmArgs& a, hipStream_t s);

@@ -1,6 +1,13 @@
 """GPU parity of the backward pass: the HIP library's gradients, through the C ABI, against the
 fp64 chain-rule oracle on the same seeded inputs.  The measure is the relative L2 error of each
-returned array; the bars are those of the forward pass (1e-5 for fp32 storage, 2e-2 for bf16)."""
+returned array; the bars are those of the forward pass (1e-5 for fp32 storage, 2e-2 for bf16).
+
+One documented exception, bf16 storage only: the head-factor gradients dU1 [nH, r1] and dU~1 are a handful
+of numbers, each a sum of signed terms sum_bc dG_i[b,c] C[a][b,c].  The bf16 storage roundings of the
+pipeline perturb the terms by about a unit roundoff (2^-9) each, so the result is off by that times the
+cancellation factor kappa = |sum of absolute terms| / |sum| (computed by the oracle in fp64).  Their bar is
+max(2e-2, 2^-10 kappa); tests/test_bf16_tolerance_model.py shows on the CPU that a plain fp64 chain rule with
+nothing but those roundings exceeds 2e-2 in such cases.  With kappa below 20 it is the common bar."""
 import numpy as np
 import pytest
 import torch
@@ -30,11 +37,23 @@ def run_backward(w, inp, dY):
 
 
 def oracle_backward(w, inp, dY):
-    return bwd.backward(inp["X"], dY, wl.weights_of(inp), w.d_head, w.causal, w.rope_base, pos0=w.pos0,
-                        shared_kv=w.shared_kv)
+    """The oracle's gradients, plus under "_bars" the bars of the head-factor gradients."""
+    wts = wl.weights_of(inp)
+    ref = bwd.backward(inp["X"], dY, wts, w.d_head, w.causal, w.rope_base, pos0=w.pos0, shared_kv=w.shared_kv,
+                       return_mixed=True)
+    dG, dGt = ref.pop("dG"), ref.pop("dGt")
+    bars = {}
+    if w.dtype == "bf16":
+        for key, mixed, core in (("dU1", dG, "C"), ("dUt1", dGt, "Ct")):
+            if np.linalg.norm(ref[key]) > 0:
+                bars[key] = max(TOL["bf16"], 2.0 ** -10 * bwd.head_factor_cancellation(mixed, wts[core]))
+    ref["_bars"] = bars
+    return ref
 
 
 def check_all(got, ref, dtype, what):
+    ref = dict(ref)
+    bars = ref.pop("_bars", {})
     assert set(got) == set(ref), (sorted(got), sorted(ref))
     errs = {}
     for k in sorted(ref):
@@ -46,8 +65,8 @@ def check_all(got, ref, dtype, what):
             errs[k] = float(np.linalg.norm(got[k]) / np.linalg.norm(ref["dX"]))
         else:
             errs[k] = orc.relative_l2(got[k], ref[k])
-    bad = {k: f"{v:.2e}" for k, v in errs.items() if v > TOL[dtype]}
-    assert not bad, f"{what}: relative L2 above {TOL[dtype]:.0e}: {bad} (all: { {k: f'{v:.1e}' for k, v in errs.items()} })"
+    bad = {k: f"{v:.2e} > {bars.get(k, TOL[dtype]):.1e}" for k, v in errs.items() if v > bars.get(k, TOL[dtype])}
+    assert not bad, f"{what}: relative L2 above its bar: {bad} (all: { {k: f'{v:.1e}' for k, v in errs.items()} })"
     return errs
 
 
@@ -178,8 +197,8 @@ def test_backward_random_small_configurations(seed):
     rt3 = r3 if shared else int(rng.choice([8, 16, 32, 56, 64, 104, 128]))
     w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=int(rng.integers(1, 5)), N=int(rng.integers(1, 300)),
                   d_model=int(rng.choice([64, 96, 200])), n_heads=int(rng.integers(1, 11)),
-                  d_head=int(rng.choice([16, 32, 64])), r1=int(rng.integers(2, 5)), r2=int(rng.choice([8, 32, 48, 80])),
-                  r3=r3, rt1=int(rng.integers(2, 5)), rt2=int(rng.choice([8, 32, 64, 100])), rt3=rt3, dtype=dtype,
+                  d_head=int(rng.choice([16, 32, 64])), r1=int(rng.integers(1, 5)), r2=int(rng.choice([8, 32, 48, 80])),
+                  r3=r3, rt1=int(rng.integers(1, 5)), rt2=int(rng.choice([8, 32, 64, 100])), rt3=rt3, dtype=dtype,
                   causal=bool(rng.integers(0, 2)), rope_base=[None, 1e4, 5e5][int(rng.integers(0, 3))],
                   seed=6000 + seed, shared_kv=shared, pos0=int(rng.integers(0, 50)))
     run_case(w, seed=7000 + seed)
@@ -188,18 +207,18 @@ def test_backward_random_small_configurations(seed):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_backward_head_rank_one(dtype):
     # r1 = 1: every head uses the same core slice, scaled by U1[i, 0].  dU1[i] = <dG_i, C[0]> is then a
-    # temperature-like gradient, sum over (query, key) of dS * S up to a factor, in which the row sums of dS
-    # cancel: with bf16 storage its few entries carry the rounding noise of the whole sum.  fp32 storage
-    # meets the common bar; for bf16 the head-factor gradients alone get 6e-2, all others the common bar.
+    # temperature-like gradient in which the row sums of dS cancel (cancellation factor about 70 here).
     w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=140, d_model=96, n_heads=6, d_head=16, r1=1, r2=80, r3=48,
                   rt1=1, rt2=8, rt3=128, dtype=dtype, rope_base=None, seed=6011)
-    inp = wl.make_inputs(w)
-    dY = upstream(w, 7011)
-    got, ref = run_backward(w, inp, dY), oracle_backward(w, inp, dY)
-    for k in ref:
-        bar = 6e-2 if (dtype == "bf16" and k in ("dU1", "dUt1")) else TOL[dtype]
-        err = orc.relative_l2(got[k], ref[k])
-        assert err <= bar, (k, err)
+    run_case(w, seed=7011)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_one_head_two_post_softmax_head_ranks(dtype):
+    # one head, r~1 = 2, value rank 8: the two numbers of dU~1 cancel by a factor of about 75
+    w = wl.scaled(wl.WORKLOADS["tiny_f32"], B=2, N=242, d_model=96, n_heads=1, d_head=64, r1=4, r2=8, r3=128,
+                  dtype=dtype, causal=False, rope_base=None, seed=6083, recipe="fan_in", rt1=2, rt2=64, rt3=8, pos0=3)
+    run_case(w, seed=7083)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

@@ -157,3 +157,28 @@ def test_causal_gradient_of_x_respects_the_mask():
     g = bwd.backward(X, dY, w, d_head=4, causal=True, rope_base=100.0)
     assert np.all(g["dX"][0, m + 1:] == 0.0)
     assert np.any(g["dX"][0, :m + 1] != 0.0)
+
+
+def test_mixed_core_gradients_and_the_cancellation_factor():
+    # identity head factors: the head-mixed core IS the core, so dG must equal dC (itself pinned by finite
+    # differences above), and likewise after the softmax
+    rng = RNG(27)
+    d, nH, N = 6, 3, 5
+    w = rand_weights(rng, d, nH, (nH, 3, 4), (nH, 5, 4))
+    w["U1"], w["Ut1"] = np.eye(nH), np.eye(nH)
+    X, dY = rng.standard_normal((2, N, d)), rng.standard_normal((2, N, d))
+    g = bwd.backward(X, dY, w, d_head=3, causal=True, rope_base=50.0, return_mixed=True)
+    assert np.allclose(g["dG"], g["dC"], rtol=0, atol=1e-12) and np.allclose(g["dGt"], g["dCt"], rtol=0, atol=1e-12)
+    fd = finite_difference(X, w, dY, "C", False, d_head=3, causal=True, rope_base=50.0)
+    assert np.max(np.abs(g["dG"] - fd)) <= 2e-7 * max(1e-3, float(np.max(np.abs(fd))))
+    # general head factors: the returned dC / dU1 are the contractions of dG the docstring states
+    w = rand_weights(rng, d, nH, (2, 3, 4), (2, 5, 4))
+    g = bwd.backward(X, dY, w, d_head=3, causal=False, return_mixed=True)
+    assert np.allclose(g["dU1"], np.einsum("ibc,abc->ia", g["dG"], w["C"]), rtol=0, atol=1e-12)
+    assert np.allclose(g["dCt"], np.einsum("ia,ibc->abc", w["Ut1"], g["dGt"]), rtol=0, atol=1e-12)
+    assert set(bwd.backward(X, dY, w, d_head=3, causal=False)) == set(g) - {"dG", "dGt"}
+    # cancellation factor by hand: terms (+3, -2) -> |3| + |-2| over |3 - 2|; same-sign terms give 1
+    assert bwd.head_factor_cancellation(np.array([[[3.0, 2.0]]]), np.array([[[1.0, -1.0]]])) == 5.0
+    assert bwd.head_factor_cancellation(np.array([[[3.0, 2.0]]]), np.array([[[1.0, 1.0]]])) == 1.0
+    two = bwd.head_factor_cancellation(np.array([[[1.0, 1.0]], [[2.0, 0.0]]]), np.array([[[1.0, -1.0]]]))
+    assert abs(two - math.sqrt(2.0 ** 2 + 2.0 ** 2) / 2.0) < 1e-15           # entries (0, 2): sums of |terms| (2, 2)
