@@ -291,6 +291,9 @@ def main():
                     help="capture the launches of one step into a HIP graph once and time replays of it (the library "
                          "only enqueues kernels on the caller's stream, so a step can be captured as it is)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="only measure what the matrix pipe of this board sustains on a bf16 MFMA loop with random "
+                         "operands (registers only, and fed from LDS like the attention kernel) and print it as JSON")
     ap.add_argument("--pmc-summary", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
                     help="no GPU work: read the counter CSVs of two rocprofv3 --pmc runs of this script (FETCH_SIZE, "
                          "WRITE_SIZE) and record HBM bytes per launch in profiles/hbm_traffic.json")
@@ -318,6 +321,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.mfma_ceiling:
+        regs = ta.tucker_attn_measure_mfma_ceiling(False)
+        lds = ta.tucker_attn_measure_mfma_ceiling(True)
+        print(json.dumps({"metric": "mfma_ceiling_bf16", "unit": "TFLOP/s", "operands_in_registers": regs,
+                          "one_operand_from_lds": lds, "published_peak": PEAK_BF16_TFLOPS,
+                          "frac_registers": regs / PEAK_BF16_TFLOPS, "frac_lds": lds / PEAK_BF16_TFLOPS,
+                          "what": "bf16 32x32x16 MFMA loop, pseudo-random operands, 8 waves per compute unit, best of 5"}),
+              flush=True)
+        return
     w = wl.WORKLOADS[args.workload]
     if args.batch > 0:
         w = wl.scaled(w, B=args.batch, name=f"{w.name}_B{args.batch}")

@@ -264,6 +264,18 @@ int tucker_attn_release_weights(tucker_attn_ctx *ctx);
 int tucker_attn_profile_enable(tucker_attn_ctx *ctx, int32_t on);
 int tucker_attn_profile_read(tucker_attn_ctx *ctx, const char **names, float *ms, int32_t n_max);
 
+/*
+ * Measurement aid, not part of the layer: the rate the matrix pipe of the current device sustains on a loop of
+ * bf16 32x32x16 MFMAs with pseudo-random operands, eight waves on every compute unit, on the null stream (the
+ * call synchronises; best of five launches).  Reports that quote a fraction of the published bf16 peak give this
+ * figure beside it (the published peak assumes the maximum clock, which a board at its power limit does not hold).
+ *   from_lds    0: both operands stay in registers; 1: one 2 KB operand fragment is re-read from LDS for every
+ *               pair of MFMAs, the way the attention kernel is fed
+ *   iters       loop length per wave (8 MFMAs each), e.g. 20000
+ *   tflops_out  host, receives TFLOP/s
+ */
+int tucker_attn_measure_mfma_ceiling(int32_t from_lds, int32_t iters, float *tflops_out);
+
 /* Static, human-readable text for a status code. */
 const char *tucker_attn_status_string(int status);
 

@@ -23,7 +23,8 @@ EXPORTED = [
     "tucker_attn_decode_workspace_bytes", "tucker_attn_forward", "tucker_attn_decode", "tucker_attn_decode_static",
     "tucker_attn_backward_workspace_bytes", "tucker_attn_backward",
     "tucker_attn_prepared_weights_bytes", "tucker_attn_prepare_weights", "tucker_attn_release_weights",
-    "tucker_attn_profile_enable", "tucker_attn_profile_read", "tucker_attn_status_string",
+    "tucker_attn_profile_enable", "tucker_attn_profile_read", "tucker_attn_measure_mfma_ceiling",
+    "tucker_attn_status_string",
 ]
 EXPORTED_CONVERT = [
     "tucker_convert_from_gqa", "tucker_convert_from_mla", "tucker_convert_hosvd_workspace_bytes",
@@ -121,6 +122,8 @@ def load_library() -> C.CDLL:
     lib.tucker_attn_profile_enable.restype = C.c_int
     lib.tucker_attn_profile_read.argtypes = [ctx_p, C.POINTER(C.c_char_p), C.POINTER(C.c_float), C.c_int32]
     lib.tucker_attn_profile_read.restype = C.c_int
+    lib.tucker_attn_measure_mfma_ceiling.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_float)]
+    lib.tucker_attn_measure_mfma_ceiling.restype = C.c_int
     lib.tucker_attn_status_string.argtypes = [C.c_int]
     lib.tucker_attn_status_string.restype = C.c_char_p
     out_p = C.POINTER(tucker_convert_weights_out)
@@ -295,6 +298,14 @@ def tucker_attn_profile_read(ctx: int) -> List[Tuple[str, float]]:
     if n < 0:
         _check(n, "tucker_attn_profile_read")
     return [(names[i].decode(), float(ms[i])) for i in range(n)]
+
+
+def tucker_attn_measure_mfma_ceiling(from_lds: bool, iters: int = 20000) -> float:
+    """TFLOP/s of a bf16 MFMA loop on the current device (operands in registers, or one re-read from LDS)."""
+    out = C.c_float()
+    _check(load_library().tucker_attn_measure_mfma_ceiling(int(bool(from_lds)), int(iters), C.byref(out)),
+           "tucker_attn_measure_mfma_ceiling")
+    return float(out.value)
 
 
 # ---- weight front-ends (include/tucker_convert.h) ------------------------------------------------
