@@ -62,23 +62,26 @@ def pmc_summary(args):
     import glob
 
     def per_kernel(root, counter):
-        tot, cnt = {}, {}
+        """mean and largest reading per kernel name, and the number of dispatches"""
+        tot, cnt, top = {}, {}, {}
         for f in glob.glob(os.path.join(root, "**", "*counter_collection.csv"), recursive=True):
             for row in csv.DictReader(open(f)):
                 if row.get("Counter_Name") != counter:
                     continue
-                k = row["Kernel_Name"]
-                tot[k] = tot.get(k, 0.0) + float(row["Counter_Value"])
+                k, v = row["Kernel_Name"], float(row["Counter_Value"])
+                tot[k] = tot.get(k, 0.0) + v
                 cnt[k] = cnt.get(k, 0) + 1
-        return {k: tot[k] / cnt[k] for k in tot}, cnt
+                top[k] = max(top.get(k, 0.0), v)
+        return {k: tot[k] / cnt[k] for k in tot}, cnt, top
 
-    fetch, nf = per_kernel(args.pmc_summary[0], "FETCH_SIZE")
-    write, nw = per_kernel(args.pmc_summary[1], "WRITE_SIZE")
+    fetch, nf, fetch_top = per_kernel(args.pmc_summary[0], "FETCH_SIZE")
+    write, nw, write_top = per_kernel(args.pmc_summary[1], "WRITE_SIZE")
     copy_bytes = args.copy_calibration_mib << 20
-    ck = [k for k in fetch if "copy" in k.lower() or "elementwise" in k.lower()]
+    # the calibration copy is the largest dispatch of the runtime's buffer-copy kernel (smaller ones move inputs)
+    ck = [k for k in fetch_top if "copybuffer" in k.lower()]
     assert ck and copy_bytes > 0, "the counter runs must include the calibration copy (--copy-calibration-mib)"
-    ck = max(ck, key=lambda k: fetch[k])
-    f_scale, w_scale = copy_bytes / (fetch[ck] * 1024.0), copy_bytes / (write[ck] * 1024.0)
+    ck = max(ck, key=lambda k: fetch_top[k])
+    f_scale, w_scale = copy_bytes / (fetch_top[ck] * 1024.0), copy_bytes / (write_top[ck] * 1024.0)
     try:
         rec = json.load(open(TRAFFIC_JSON))
     except (OSError, ValueError):
