@@ -37,6 +37,7 @@ struct tucker_attn_ctx {
   int es;                      // bytes per stored element
   float4* rope;                // device [D/4][max_positions] (cos, sin, cos, sin) or null
   float qscale;                // log2(e) / sqrt(d_head), folded into the head-mixed core
+  int n_cus;                   // compute units of the device current at create (256 if none could be asked)
   int profile;
   int n_kernels;
   const char* names[kMaxKernels];
@@ -198,11 +199,18 @@ BackwardWs carve_backward(const tucker_attn_ctx* c, void* ws, int B, int N) {
   return w;
 }
 
-int decode_nsplit(int B) {
-  int n = 512 / B;
-  if (n < 1) n = 1;
+// Workgroups per sequence of the split-KV decode attention.  Measured at 16 sequences x 32768 cached tokens on a
+// board of 256 compute units: 256 workgroups in all (one per compute unit) 54 us, 512: 57 us, 128: 90 us, counts
+// that are no multiple of the number of compute units (192, 320, 384): 64-79 us.  So one round over the compute
+// units, and never more splits than the longest cache has 64-key tiles.  The shared-latent variant rotates keys as
+// it stages them and is bound by that arithmetic, not by HBM: it runs two rounds (52 us against 68 with one).  At
+// most 64 splits: the merge kernel walks them one after the other (256 splits of one 128k-token sequence: 34 us).
+int decode_nsplit(const tucker_attn_ctx* c, int B, int longest) {
+  int n = (c->cfg.shared_kv ? 2 : 1) * c->n_cus / B;
+  const long tiles = ((long)longest + 63) / 64;
   if (n > 64) n = 64;
-  return n;
+  if (n > tiles) n = (int)tiles;
+  return n < 1 ? 1 : n;
 }
 int decode_ksplit(int K) {
   int nk = (K + 63) / 64;
@@ -212,7 +220,7 @@ int decode_ksplit(int K) {
 DecodeWs carve_decode(const tucker_attn_ctx* c, void* ws, int B) {
   const tucker_attn_config& f = c->cfg;
   const int HB32 = pad32(f.n_heads);
-  const int ns = decode_nsplit(B);
+  const int ns = decode_nsplit(c, B, 1 << 30);                     // the most a call can use
   Carver cv{static_cast<char*>(ws), 0};
   DecodeWs w;
   carve_weights(c, cv, w.Gt, w.Gtil2, w.Wcat, w.Ut2p);
@@ -391,6 +399,8 @@ int decode_impl(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x,
     char* Kb = static_cast<char*>(Kcache) + (size_t)b0 * Lmax * f.r3 * c->es;
     char* Vb = Vcache ? static_cast<char*>(Vcache) + (size_t)b0 * Lmax * f.rt3 * c->es : nullptr;
     const int32_t* len = kv_len + b0;
+    int longest = 1;
+    for (int b = 0; b < Bc; ++b) longest = len[b] > longest ? len[b] : longest;
 
     const void* ut2;
     long ut2_ld;
@@ -419,7 +429,7 @@ int decode_impl(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x,
     d.Qlat = ws.Qlat; d.Gt = ws.Gt; d.Qh = ws.Qh; d.Kcache = Kb; d.Vcache = Vb;
     d.part_m = ws.pm; d.part_l = ws.pl; d.part_o = ws.po; d.O = ws.O; d.rope = c->rope; d.rope_ld = f.max_positions;
     d.Bsz = Bc; d.nH = f.n_heads; d.HB = pad32(f.n_heads) / 32; d.R2 = c->R2; d.r3 = f.r3; d.rt3 = f.rt3;
-    d.D = c->D; d.Lmax = Lmax; d.nsplit = decode_nsplit(Bc); d.shared_kv = f.shared_kv;
+    d.D = c->D; d.Lmax = Lmax; d.nsplit = decode_nsplit(c, Bc, longest); d.shared_kv = f.shared_kv;
     for (int b = 0; b < Bc; ++b) d.kv_len[b] = len[b];
     if (launch_decode_qhat(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
     rec.after("decode_query");
@@ -486,6 +496,15 @@ int tucker_attn_create(const tucker_attn_config* cfg, tucker_attn_ctx** out) {
   c->dp = pad32(f.d_model);
   c->es = f.dtype == TUCKER_ATTN_F32 ? 4 : 2;
   c->qscale = (float)(1.4426950408889634 / std::sqrt((double)f.d_head));
+  c->n_cus = 256;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      c->n_cus = cus;
+    else
+      (void)hipGetLastError();
+  }
   c->rope = nullptr;
   if (f.use_rope) {
     // angle = position * base^(-2j/r3), evaluated in double precision, stored as fp32.  Entry
