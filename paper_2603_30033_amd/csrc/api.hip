@@ -202,12 +202,17 @@ BackwardWs carve_backward(const tucker_attn_ctx* c, void* ws, int B, int N) {
 // Workgroups per sequence of the split-KV decode attention.  Measured at 16 sequences x 32768 cached tokens on a
 // board of 256 compute units: 256 workgroups in all (one per compute unit) 54 us, 512: 57 us, 128: 90 us, counts
 // that are no multiple of the number of compute units (192, 320, 384): 64-79 us.  So one round over the compute
-// units, and never more splits than the longest cache has 64-key tiles.  The shared-latent variant rotates keys as
-// it stages them and is bound by that arithmetic, not by HBM: it runs two rounds (52 us against 68 with one).  At
-// most 64 splits: the merge kernel walks them one after the other (256 splits of one 128k-token sequence: 34 us).
+// units, and never more splits than the longest cache has 64-key tiles.  The shared-latent variant of that kernel
+// rotates keys as it stages them and is bound by that arithmetic, not by HBM: it runs two rounds (52 us against 68
+// with one); the wave-private shared-latent kernel holds one workgroup per compute unit and takes 128 keys at a
+// time.  At most 64 splits: the merge kernel walks them one after the other (256 splits of one 128k-token
+// sequence: 34 us).
 int decode_nsplit(const tucker_attn_ctx* c, int B, int longest) {
-  int n = (c->cfg.shared_kv ? 2 : 1) * c->n_cus / B;
-  const long tiles = ((long)longest + 63) / 64;
+  const tucker_attn_config& f = c->cfg;
+  const bool wave_private = decode_wave_private(f.dtype, f.r3, c->D, f.shared_kv);
+  int n = (f.shared_kv && !wave_private ? 2 : 1) * c->n_cus / B;
+  const int step = wave_private ? kDecodeRoundWave : kDecodeTile;  // keys a workgroup takes at a time
+  const long tiles = ((long)longest + step - 1) / step;
   if (n > 64) n = 64;
   if (n > tiles) n = (int)tiles;
   return n < 1 ? 1 : n;

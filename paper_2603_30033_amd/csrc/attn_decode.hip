@@ -332,6 +332,295 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeArgs p) {
 }
 
 // ---------------------------------------------------------------------------------------
+// split-KV attention over a shared key-value latent, bf16, cache rows exactly D wide
+// ---------------------------------------------------------------------------------------
+// With one cache to read, a step has half the bytes to stream and the arithmetic per byte doubles: the
+// kernel above (every wave computes every score of a tile) is then bound by its own instructions.  Here
+// the slice of a workgroup is walked in rounds of 128 keys; wave w owns keys 32w .. 32w+31 of every round
+// and does ALL the work for them: scores against every head, its own running softmax, and the product
+// with the values for all D channels.  Nothing is shared between the waves while they stream, so there is
+// no barrier in the loop and no score is computed twice; the four partial results are merged through LDS
+// once at the end.  A wave moves its 32 cache rows from global memory straight into one of its two LDS
+// stages (no registers in between), two rounds ahead.  The tile serves as value tile as it stands
+// (transposing reads) and as key tile, its fragments being rotated in registers by the angle of
+// (first key of the tile) + (row): the entries of the first come with the tile as one extra 1 KB piece of
+// the rotation table (one 16-byte entry per channel quad), those of the second are the same for every tile
+// and sit in an LDS table that all waves read.
+template <int D, bool ROT> struct DecWaveLds {
+  static constexpr int kTile = 32 * D;                            // elements of a 32-key tile
+  static constexpr int kRot = ROT ? 512 : 0;                      // one 1 KB piece of table entries
+  static constexpr int kStage = kTile + kRot;
+  static constexpr size_t kStagesBytes = 4ul * 2 * kStage * sizeof(bf16);
+  // ROT: behind the stages, the rotation of every tile row, [D/4 quads][32 rows] x 16 bytes
+  static constexpr size_t kRowTabBytes = ROT ? (size_t)(D / 4) * 32 * 16 : 0;
+  static constexpr size_t pipeline_bytes() { return kStagesBytes + kRowTabBytes; }
+  static constexpr size_t merge_bytes(int HB) { return 4ul * HB * 32 * (D + 4 + 2) * sizeof(float); }
+  static constexpr size_t bytes(int HB) { return pipeline_bytes() > merge_bytes(HB) ? pipeline_bytes() : merge_bytes(HB); }
+};
+
+// at most N vector-memory operations of this wave (loads, direct-to-LDS loads) still in flight
+template <int N> __device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N < 64, "six-bit counter");
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+  asm volatile("" ::: "memory");
+}
+// every LDS read of this wave has returned
+__device__ __forceinline__ void wait_lds() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  asm volatile("" ::: "memory");
+}
+
+// Up to 32 heads the kernel is held to 256 registers: with more, the compiler parks values in accumulation
+// registers and pays a copy for every use by the vector unit.
+template <int D, int HB, bool ROT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HB == 1 ? 2 : 1, HB == 1 ? 2 : 1)))
+void decode_attn_shared_kernel(DecodeArgs p) {
+  using T = bf16;
+  using L = DecWaveLds<D, ROT>;
+  constexpr int CB = D / 32, CPR = D / 8;
+  constexpr int PIECES = L::kTile / 512;                          // 1 KB pieces of a tile
+  constexpr int HB32 = HB * 32;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+  const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int h = lane / 32, lr = lane % 32;
+  const int b = blockIdx.y, split = blockIdx.x;
+  const int Lb = p.kv_len[b];
+  const int rounds_all = (Lb + kDecodeRoundWave - 1) / kDecodeRoundWave;
+  const int per = (rounds_all + p.nsplit - 1) / p.nsplit;
+  const int r_first = split * per, r_last = min(rounds_all, r_first + per);
+  const int cnt = max(r_last - r_first, 0);                       // rounds of this workgroup
+
+  float* pm = p.part_m + ((long)b * p.nsplit + split) * HB32;
+  float* pl = p.part_l + ((long)b * p.nsplit + split) * HB32;
+  float* po = p.part_o + ((long)b * p.nsplit + split) * HB32 * D;
+
+  f32x16 oacc[HB][CB];
+  float m_run[HB], l_run[HB];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    m_run[hb] = -INFINITY;
+    l_run[hb] = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[hb][cb][e] = 0.f;
+  }
+
+  if (cnt > 0) {                                                  // (the same for the whole workgroup)
+    T* wbase = reinterpret_cast<T*>(smem_raw) + (long)wave * 2 * L::kStage;
+    const T* Lc = static_cast<const T*>(p.Kcache) + (long)b * p.Lmax * D;
+    // The slices of different workgroups lie a power of two apart in memory: each workgroup starts at
+    // its own round of its slice and wraps around (the online softmax does not care about order).
+    const int first = (int)((split * 5u + b * 3u) % (unsigned)cnt);
+    auto block_at = [&](int j) {                                  // this wave's 32-key block of round j
+      int r = min(j, cnt - 1) + first;                            // past the end: the last round again (not used)
+      if (r >= cnt) r -= cnt;
+      return (r_first + r) * 4 + wave;
+    };
+    // Rows past the end of the sequence read its last row (they are masked below), so every address stays
+    // inside the rows the sequence owns.
+    auto issue = [&](int j, int st) {
+      const int n0 = block_at(j) * 32;
+      T* kt = wbase + (long)st * L::kStage;
+#pragma unroll
+      for (int q = 0; q < PIECES; ++q)
+        dma_piece<T, CPR>(kt, q, lane, [&](int row) { return Lc + (long)min(n0 + row, Lb - 1) * D; });
+      if constexpr (ROT) {
+        const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope) + (long)min(lane % 32, D / 4 - 1) * p.rope_ld +
+                           min(n0, p.rope_ld - 1);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)tab,
+                                         (__attribute__((address_space(3))) void*)(kt + L::kTile), 16, 0, 0);
+      }
+    };
+    // direct-to-LDS loads of one stage; while a stage is read, at most the other one may still be in flight
+    constexpr int OPS = PIECES + (ROT ? 1 : 0);
+
+    // query fragments: lane = head, natural order in c
+    Frag<T> qf[HB][CB];
+    {
+      const T* Qh = static_cast<const T*>(p.Qh) + (long)b * HB32 * D;
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) qf[hb][cb] = load_frag<T>(Qh + (long)(hb * 32 + lr) * D + cb * 32 + 16 * h);
+    }
+    f32x4* rowtab = reinterpret_cast<f32x4*>(smem_raw + L::kStagesBytes);
+    if constexpr (ROT) {
+      for (int i = threadIdx.x; i < (D / 4) * 32; i += 256)
+        rowtab[i] = reinterpret_cast<const f32x4*>(p.rope)[(long)(i / 32) * p.rope_ld + min(i % 32, p.rope_ld - 1)];
+    }
+    wait_vm<0>();                                                 // plain loads out of the way of the counted ones
+    if constexpr (ROT) __syncthreads();
+    issue(0, 0);
+    issue(1, 1);
+
+    constexpr float kLazy = 8.f;
+    const int xs = swz_x<CPR>(lr);
+    auto round = [&](int j, int st) {
+      const int n0 = block_at(j) * 32;
+      const T* kt = wbase + (long)st * L::kStage;
+      wait_vm<OPS>();
+      f32x16 s[HB];
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[hb][e] = 0.f;
+      if constexpr (ROT) {
+        // one 32-channel block at a time, the operands of the next one requested before this one is rotated:
+        // key fragment, the tile's entries (angle of its first key) and the row's entries of 4 channel quads
+        struct In { Frag<T> k; f32x4 t[4], a[4]; };
+        const f32x4* rl = reinterpret_cast<const f32x4*>(kt + L::kTile);
+        auto fetch = [&](int cb) {
+          In in;
+          in.k = load_frag_swz<T>(kt + lr * D, 4 * cb + 2 * h, xs);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            in.t[q] = rl[8 * cb + 4 * h + q];
+            in.a[q] = rowtab[(8 * cb + 4 * h + q) * 32 + lr];
+          }
+          return in;
+        };
+        In cur = fetch(0);
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+          In nxt = cur;
+          if (cb + 1 < CB) nxt = fetch(cb + 1);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            u32x4 raw = __builtin_bit_cast(u32x4, cur.k.v[i]);
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+              // dword d of chunk i: channel pair 4i+d of this lane's 8 pairs = quad 2i + d/2, entry (d%2)
+              const f32x4 a = cur.a[2 * i + d / 2], t = cur.t[2 * i + d / 2];
+              const int e = 2 * (d % 2);
+              const float c = a[e] * t[e] - a[e + 1] * t[e + 1], sn = a[e + 1] * t[e] + a[e] * t[e + 1];
+              const float x0 = __uint_as_float(raw[d] << 16), x1 = __uint_as_float(raw[d] & 0xffff0000u);
+              f32x2 two = {x0 * c - x1 * sn, x0 * sn + x1 * c};
+              raw[d] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
+            }
+            cur.k.v[i] = __builtin_bit_cast(bf16x8, raw);
+          }
+#pragma unroll
+          for (int hb = 0; hb < HB; ++hb) mma32(s[hb], cur.k, qf[hb][cb]);
+          __builtin_amdgcn_sched_barrier(0);
+          cur = nxt;
+        }
+      } else {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+          const Frag<T> kf = load_frag_swz<T>(kt + lr * D, 4 * cb + 2 * h, xs);
+#pragma unroll
+          for (int hb = 0; hb < HB; ++hb) mma32(s[hb], kf, qf[hb][cb]);
+        }
+      }
+      // the value fragments (transposing reads of the same tile) are taken before the stage is refilled
+      FragTrPending vp[CB];
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) vp[cb] = load_frag_tr_swz_start<CPR>(kt, 0, cb * 32, lane);
+      wait_lds();
+      issue(j + 2, st);
+      Frag<T> vf[CB];
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) vf[cb] = load_frag_tr_finish(vp[cb]);
+
+      if (n0 + 32 > Lb) {
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (n0 + 8 * (e / 4) + 4 * h + (e % 4) >= Lb) s[hb][e] = -INFINITY;
+      }
+      // online softmax with a lazily raised reference: O and l are rescaled only when a block's maximum
+      // exceeds the reference by more than kLazy (probabilities stay below 2^kLazy)
+      Frag<T> pf[HB];
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[hb][e]);
+        mx = halves_max(mx);
+        const bool upd = mx > m_run[hb] + kLazy;                  // -inf + kLazy = -inf: the first live block updates
+        if (__builtin_amdgcn_ballot_w64(upd) != 0ull) {
+          const float alpha = upd ? fast_exp2(m_run[hb] - mx) : 1.f;   // exp2(-inf) = 0: O and l are still zero
+          if (upd) m_run[hb] = mx;
+          l_run[hb] *= alpha;
+#pragma unroll
+          for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[hb][cb][e] *= alpha;
+        }
+        const float m_use = (m_run[hb] == -INFINITY) ? 0.f : m_run[hb];
+        float rs = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          s[hb][e] = fast_exp2(s[hb][e] - m_use);
+          rs += s[hb][e];
+        }
+        l_run[hb] += rs;
+        pf[hb] = to_frag<T>(s[hb]);
+      }
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) mma32(oacc[hb][cb], vf[cb], pf[hb]);
+    };
+    for (int j = 0; j < cnt; j += 2) {                            // the stage index is a constant in each call
+      round(j, 0);
+      if (j + 1 < cnt) round(j + 1, 1);
+    }
+    wait_vm<0>();                                                 // tiles requested past the end still land in LDS
+  }
+  __syncthreads();
+
+  // ---- merge of the four waves' partial results through LDS -> one partial per workgroup ----
+  constexpr int RE = D + 4;                                       // padded row of a wave's O[head][c]
+  float* mo = reinterpret_cast<float*>(smem_raw);                 // [4][HB32][RE]
+  float* mm = mo + 4 * HB32 * RE;                                 // [4][HB32] references, then [4][HB32] sums
+  float* ml = mm + 4 * HB32;
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    const float l_tot = halves_sum(l_run[hb]);
+    if (h == 0) {
+      mm[wave * HB32 + hb * 32 + lr] = m_run[hb];
+      ml[wave * HB32 + hb * 32 + lr] = l_tot;
+    }
+    float* row = mo + ((long)wave * HB32 + hb * 32 + lr) * RE;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<f32x4*>(row + cb * 32 + 8 * q + 4 * h) =
+            f32x4{oacc[hb][cb][4 * q], oacc[hb][cb][4 * q + 1], oacc[hb][cb][4 * q + 2], oacc[hb][cb][4 * q + 3]};
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < HB32 * D; idx += 256) {
+    const int hd = idx / D, c = idx % D;
+    float mw[4], mx = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      mw[w] = mm[w * HB32 + hd];
+      mx = fmaxf(mx, mw[w]);
+    }
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = mw[w] == -INFINITY ? 0.f : fast_exp2(mw[w] - mx);
+      num += f * mo[((long)w * HB32 + hd) * RE + c];
+      den += f * ml[w * HB32 + hd];
+    }
+    po[idx] = num;
+    if (c == 0) {
+      pm[hd] = mx;
+      pl[hd] = den;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // merge of split partials -> O[b][head][c] (c stored in acc order for the latent merge GEMM)
 // ---------------------------------------------------------------------------------------
 template <typename T>
@@ -430,7 +719,38 @@ static hipError_t attn_dispatch(const DecodeArgs& a, hipStream_t s) {
   }
   return hipErrorInvalidValue;
 }
+template <int D, int HB, bool ROT>
+static hipError_t shared_one(const DecodeArgs& a, hipStream_t s) {
+  const size_t smem = DecWaveLds<D, ROT>::bytes(HB);
+  auto kern = decode_attn_shared_kernel<D, HB, ROT>;
+  static LdsOnce lds_once;                                       // one per kernel instantiation
+  if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
+  hipLaunchKernelGGL(kern, dim3(a.nsplit, a.Bsz), dim3(256), smem, s, a);
+  return hipGetLastError();
+}
+template <int D, int HB>
+static hipError_t shared_variant(const DecodeArgs& a, hipStream_t s) {
+  return a.rope != nullptr ? shared_one<D, HB, true>(a, s) : shared_one<D, HB, false>(a, s);
+}
+static hipError_t shared_dispatch(const DecodeArgs& a, hipStream_t s) {
+  if (a.HB == 1) {
+    switch (a.D) {
+      case 32: return shared_variant<32, 1>(a, s);
+      case 64: return shared_variant<64, 1>(a, s);
+      case 128: return shared_variant<128, 1>(a, s);
+    }
+  } else if (a.HB == 2) {
+    switch (a.D) {
+      case 32: return shared_variant<32, 2>(a, s);
+      case 64: return shared_variant<64, 2>(a, s);
+      case 128: return shared_variant<128, 2>(a, s);
+    }
+  }
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s) {
+  if (decode_wave_private(dtype, a.r3, a.D, a.shared_kv)) return shared_dispatch(a, s);
   return dtype == 0 ? attn_dispatch<float, 32>(a, s) : attn_dispatch<bf16, 64>(a, s);
 }
 

@@ -260,6 +260,33 @@ __device__ __forceinline__ Frag<float> load_frag_tr_swz(const float* tile, int r
     }
   return f;
 }
+// The same transposed fragment read in two steps, for loops that keep direct global-to-LDS loads in flight
+// while they read: the compiler puts a wait for ALL outstanding direct-to-LDS loads in front of the
+// transposing-read builtin.  `start` only issues the four reads (the compiler does not see them as LDS reads);
+// `finish` waits until every LDS read of the wave has returned and hands the fragment over.  Nothing may touch
+// the result of `start` except `finish`.
+struct FragTrPending { u32x2 q[4]; };
+template <int CPR>
+__device__ __forceinline__ FragTrPending load_frag_tr_swz_start(const bf16* tile, int row0, int col0, int lane) {
+  const int h = lane / 32, i = lane % 16;
+  const int col = col0 + (lane & 16) + 4 * (i % 4);
+  FragTrPending f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = row0 + 8 * q + 4 * h + i / 4;
+    const bf16* src = tile + row * (CPR * 8) + (((col / 8) ^ swz_x<CPR>(row)) * 8) + col % 8;
+    const uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const bf16*)src;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.q[q]) : "v"(addr) : "memory");
+  }
+  return f;
+}
+__device__ __forceinline__ Frag<bf16> load_frag_tr_finish(FragTrPending& f) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.q[0]), "+v"(f.q[1]), "+v"(f.q[2]), "+v"(f.q[3]) : : "memory");
+  Frag<bf16> r;
+  r.v[0] = __builtin_bit_cast(bf16x8, u32x4{f.q[0][0], f.q[0][1], f.q[1][0], f.q[1][1]});
+  r.v[1] = __builtin_bit_cast(bf16x8, u32x4{f.q[2][0], f.q[2][1], f.q[3][0], f.q[3][1]});
+  return r;
+}
 // one direct global-to-LDS load of this wave: 64 consecutive chunks of a swizzled tile starting at
 // chunk q*64; `row_ptr(row)` gives the global address of tile row `row`
 template <typename T, int CPR, class RowPtr>

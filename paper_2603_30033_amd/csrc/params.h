@@ -162,6 +162,14 @@ struct DecodeArgs {
   int kv_len[32];
 };
 
+// Which attention kernel a decode step runs.  A bf16 shared-latent cache whose rows are exactly D wide (a rank
+// that is a multiple of 32) takes the wave-private kernel, which walks a slice in rounds of kDecodeRoundWave keys;
+// any other configuration takes the workgroup-tile kernel (range-checked loads, tiles of kDecodeTile keys).
+constexpr int kDecodeRoundWave = 128, kDecodeTile = 64;
+inline bool decode_wave_private(int dtype, int r3, int D, int shared_kv) {
+  return dtype == 1 && shared_kv && r3 == D;
+}
+
 // Raise a kernel's dynamic-LDS limit to `bytes`, once per kernel and device (the attribute belongs
 // to the device's copy of the code object).  `once` is a static of the launcher of that one
 // kernel instantiation.  Safe to call from several host threads.

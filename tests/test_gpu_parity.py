@@ -454,6 +454,20 @@ def test_decode_edge_lengths_and_many_heads(dtype):
     check_decode(base, inp, "decode 40 heads")
 
 
+@pytest.mark.parametrize("shared,rope", [(False, 1e4), (True, 1e4), (True, None)])
+@pytest.mark.parametrize("n_heads", [5, 40])
+@pytest.mark.parametrize("r3", [32, 64, 128])
+def test_decode_bf16_full_width_cache_rows(r3, n_heads, shared, rope):
+    # bf16 caches whose rows are whole 32-channel blocks take a kernel of their own (every wave streams its own
+    # keys); lengths around its 32-key blocks and 128-key rounds, a single key, and more splits than rounds
+    base = wl.scaled(wl.WORKLOADS["decode_32k_shared_kv" if shared else "decode_32k"], d_model=128, n_heads=n_heads,
+                     d_head=32, r1=3, r2=32, r3=r3, rt1=2, rt2=32, rt3=r3, B=7, kv_len=1100, dtype="bf16",
+                     rope_base=rope, seed=31 + r3 + n_heads, recipe="fan_in")
+    inp = wl.make_inputs(base)
+    inp["kv_len"] = np.array([1100, 1, 31, 33, 128, 129, 517], dtype=np.int32)
+    (check_decode_shared if shared else check_decode)(base, inp, "decode, full-width rows")
+
+
 @pytest.mark.parametrize("shared", [False, True])
 def test_decode_more_than_32_sequences(shared):
     # 70 sequences = two full passes of 32 and a ragged one, each sequence with its own cache length
