@@ -393,10 +393,6 @@ void decode_attn_shared_kernel(DecodeArgs p) {
   const int r_first = split * per, r_last = min(rounds_all, r_first + per);
   const int cnt = max(r_last - r_first, 0);                       // rounds of this workgroup
 
-  float* pm = p.part_m + ((long)b * p.nsplit + split) * HB32;
-  float* pl = p.part_l + ((long)b * p.nsplit + split) * HB32;
-  float* po = p.part_o + ((long)b * p.nsplit + split) * HB32 * D;
-
   f32x16 oacc[HB][CB];
   float m_run[HB], l_run[HB];
 #pragma unroll
@@ -577,6 +573,11 @@ void decode_attn_shared_kernel(DecodeArgs p) {
   __syncthreads();
 
   // ---- merge of the four waves' partial results through LDS -> one partial per workgroup ----
+  // The lane index is formed afresh (from the execution mask, not from the thread index): every register the
+  // loop above can have is in use, and an index kept across it would be spilled to scratch memory.
+  const int lane_m = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  const int tid_m = wave * kWave + lane_m;
+  const int h_m = lane_m / 32, lr_m = lane_m % 32;
   constexpr int RE = D + 4;                                       // padded row of a wave's O[head][c]
   float* mo = reinterpret_cast<float*>(smem_raw);                 // [4][HB32][RE]
   float* mm = mo + 4 * HB32 * RE;                                 // [4][HB32] references, then [4][HB32] sums
@@ -584,20 +585,24 @@ void decode_attn_shared_kernel(DecodeArgs p) {
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
     const float l_tot = halves_sum(l_run[hb]);
-    if (h == 0) {
-      mm[wave * HB32 + hb * 32 + lr] = m_run[hb];
-      ml[wave * HB32 + hb * 32 + lr] = l_tot;
+    if (h_m == 0) {
+      mm[wave * HB32 + hb * 32 + lr_m] = m_run[hb];
+      ml[wave * HB32 + hb * 32 + lr_m] = l_tot;
     }
-    float* row = mo + ((long)wave * HB32 + hb * 32 + lr) * RE;
+    float* row = mo + ((long)wave * HB32 + hb * 32 + lr_m) * RE;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
       for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<f32x4*>(row + cb * 32 + 8 * q + 4 * h) =
+        *reinterpret_cast<f32x4*>(row + cb * 32 + 8 * q + 4 * h_m) =
             f32x4{oacc[hb][cb][4 * q], oacc[hb][cb][4 * q + 1], oacc[hb][cb][4 * q + 2], oacc[hb][cb][4 * q + 3]};
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < HB32 * D; idx += 256) {
+  const long part = (long)blockIdx.y * p.nsplit + blockIdx.x;    // (formed here, not above: nothing to keep across the loop)
+  float* pm = p.part_m + part * HB32;
+  float* pl = p.part_l + part * HB32;
+  float* po = p.part_o + part * HB32 * D;
+  for (int idx = tid_m; idx < HB32 * D; idx += 256) {
     const int hd = idx / D, c = idx % D;
     float mw[4], mx = -INFINITY;
 #pragma unroll
