@@ -440,16 +440,22 @@ def main():
             torch.cuda.synchronize()
             return [a.elapsed_time(b) for a, b in ev]
 
-        # Clock warm-up (untimed, before --warmup): the first launches after idle run at a lower shader clock.
-        # Blocks of 10 steps are run until the median of a block is within 1 % of the previous block's, at most
-        # 40 blocks.
-        clock_steps, prev = 0, None
-        for _ in range(40):
-            cur = float(np.median(event_times(10)))
+        # Clock warm-up (untimed, before --warmup): the first launches after idle run at a lower shader clock, and
+        # under back-to-back launches the clock then settles at what the power limit allows.  Blocks of 10
+        # back-to-back steps (timed as the K steps below are: wall clock, device synchronised on both sides) are
+        # run until the last three blocks agree within 1 %, at least 5 and at most 60 blocks.
+        clock_steps, blocks = 0, []
+        for _ in range(60):
+            torch.cuda.synchronize()
+            tb = time.perf_counter()
+            for _ in range(10):
+                timed_step()
+            torch.cuda.synchronize()
+            blocks.append(time.perf_counter() - tb)
             clock_steps += 10
-            if prev is not None and abs(cur - prev) <= 0.01 * prev:
+            last = blocks[-3:]
+            if len(blocks) >= 5 and max(last) - min(last) <= 0.01 * min(last):
                 break
-            prev = cur
         for _ in range(W):
             timed_step()
         torch.cuda.synchronize()

@@ -498,6 +498,10 @@ hipError_t launch_gemm(int dtype, const GemmArgs& a, int tile_n, hipStream_t s) 
   // every compute unit two workgroups)
   if (tile_n == 64 && m_rows > 128 && m_rows <= 192 && ((long)a.Bsz * a.Npad + 63) / 64 >= 512)
     return launch_one<bf16, 192, 64, 2, 2>(a, m_rows, s);
+  // An odd number of 128-row tiles that is a whole number of 192-row tiles (384 rows: query, key and value
+  // factors of 128 each): 192-row tiles give an even workgroup count (256 instead of 384 at 8192 tokens, one per
+  // compute unit instead of one and a half) and 13 % fewer bytes from L2 into LDS; 49.4 against 51.9 us there
+  if (tile_n == 64 && m_rows % 192 == 0 && (m_rows / 128) % 2 == 1) return launch_one<bf16, 192, 64, 2, 2>(a, m_rows, s);
   if (tile_n >= 128) return launch_one<bf16, 128, 128, 2, 2>(a, m_rows, s);
   if (tile_n >= 64) return launch_one<bf16, 128, 64, 2, 2>(a, m_rows, s);
   return launch_one<bf16, 128, 32, 4, 1>(a, m_rows, s);
