@@ -469,18 +469,23 @@ def main():
         per_step = event_times(K)
         median_ms, min_ms = float(np.median(per_step)), float(np.min(per_step))
 
-        # per-kernel durations: the same K steps again with HIP events around every launch
-        ta.tucker_attn_profile_enable(layer.ctx, True)
+        # per-kernel durations: K more steps with HIP events around every launch.  Reading a step's events
+        # means waiting for it, and a step that starts on an idle device runs at another clock than one in a
+        # back-to-back stream (the attention launch was seen 10 % slower that way), so every profiled step is
+        # preceded by three ordinary ones queued with it.
         acc = {}
         order = []
         for _ in range(K):
+            for _ in range(3):
+                step()
+            ta.tucker_attn_profile_enable(layer.ctx, True)
             step()
             for name, t in ta.tucker_attn_profile_read(layer.ctx):
                 if name not in acc:
                     acc[name] = 0.0
                     order.append(name)
                 acc[name] += t
-        ta.tucker_attn_profile_enable(layer.ctx, False)
+            ta.tucker_attn_profile_enable(layer.ctx, False)
         kern_ms = {n: acc[n] / K for n in order}
 
     total_flops = fb["total"] if backward else fl["total"]
