@@ -434,19 +434,20 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(GemmArgs g) {
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   if (tp < TP) {
-    // four splits at a time: their 16 loads are issued before the first add, and the sums are still
-    // formed in split order
-    for (int z0 = 0; z0 < g.ksplit; z0 += 4) {
-      f32x4 v[4][4];
+    // eight splits at a time: their 32 loads are issued before the first add (a launch this small is all
+    // round trips to memory), and the sums are still formed in split order
+    constexpr int U = 8;
+    for (int z0 = 0; z0 < g.ksplit; z0 += U) {
+      f32x4 v[U][4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < U; ++u) {
         const int z = min(z0 + u, g.ksplit - 1);
         const float* src = g.part + ((long)z * TP + tp) * Mp + m0 + 4 * h;
 #pragma unroll
         for (int q = 0; q < 4; ++q) v[u][q] = *reinterpret_cast<const f32x4*>(src + 8 * q);
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < U; ++u)
         if (z0 + u < g.ksplit)
 #pragma unroll
           for (int q = 0; q < 4; ++q)
