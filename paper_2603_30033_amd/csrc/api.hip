@@ -237,7 +237,7 @@ DecodeWs carve_decode(const tucker_attn_ctx* c, void* ws, int B) {
   w.pl = cv.take<float>((size_t)B * ns * HB32 * 4);
   w.po = cv.take<float>((size_t)B * ns * HB32 * c->D * 4);
   const size_t p1 = (size_t)decode_ksplit(f.d_model) * B * (c->R2 + 2 * c->D) * 4;
-  const size_t p2 = (size_t)decode_ksplit(f.n_heads * c->D) * B * c->RT2 * 4;
+  const size_t p2 = (size_t)f.n_heads * B * c->RT2 * 4;            // one contribution to Z per head
   w.part = cv.take<float>(p1 > p2 ? p1 : p2);
   w.bytes = cv.off;
   return w;
@@ -440,26 +440,13 @@ int decode_impl(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x,
     rec.after("decode_query");
     if (launch_decode_attn(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
     rec.after("decode_attention");
-    if (launch_decode_merge(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    // merge of the split partials and the head merge: one workgroup per head writes its contribution to Z
+    d.Gtil2 = ws.Gtil2; d.zpart = ws.part; d.RT2 = c->RT2;
+    if (launch_decode_merge_heads(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
     rec.after("decode_merge");
-
-    GemmArgs z;
-    std::memset(&z, 0, sizeof(z));
-    z.A = ws.Gtil2; z.lda = (long)f.n_heads * c->D; z.M = c->RT2;
-    z.Bsrc = ws.O; z.ldb = (long)f.n_heads * c->D; z.K = f.n_heads * c->D;
-    z.Bsz = Bc; z.N = 1; z.Npad = 1; z.src_padded = 1;
-    z.epi = 1; z.Out = ws.Z; z.ldo = c->RT2;
-    z.ksplit = decode_ksplit(z.K); z.part = ws.part;
-    if (launch_gemm(f.dtype, z, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
-    rec.after("latent_merge");
-
-    GemmArgs yy;
-    std::memset(&yy, 0, sizeof(yy));
-    yy.A = ut2; yy.lda = ut2_ld; yy.M = f.d_model;
-    yy.Bsrc = ws.Z; yy.ldb = c->RT2; yy.K = c->RT2;
-    yy.Bsz = Bc; yy.N = 1; yy.Npad = 1; yy.src_padded = 1;
-    yy.epi = 2; yy.Out = yb; yy.ldo = f.d_model; yy.ksplit = 1;
-    if (launch_gemm(f.dtype, yy, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    // the output projection sums the heads' contributions itself
+    d.Ut2 = ut2; d.ut2_ld = ut2_ld; d.Y = yb; d.d_model = f.d_model;
+    if (launch_decode_out(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
     rec.after("output_projection");
   }
   return TUCKER_ATTN_OK;

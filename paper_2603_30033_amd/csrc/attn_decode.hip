@@ -672,6 +672,173 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs p) {
 }
 
 // ---------------------------------------------------------------------------------------
+// merge of split partials and head merge in one launch: one workgroup per head
+// ---------------------------------------------------------------------------------------
+// The workgroup of head i merges the split partials of its head for every sequence (as decode_merge
+// does), keeps the normalised O_i [sequence][c] in LDS in operand order, and multiplies it by the head's
+// post-softmax core: Zpart_i^T[b][sequence] = sum_c G~_i[b][c] O_i[sequence][c].  The per-head
+// contributions are written where a split-K product would put its partial tiles ([head][sequence][RT2],
+// fp32), and the split-K reduction sums them over heads into Z.  This replaces two launches (the merge and
+// a product that streams all heads' cores through a few workgroups) by one in which every head's 32 KB core
+// block is read by its own workgroup.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_merge_heads_kernel(DecodeArgs p) {
+  constexpr int CB = D / 32, CPT = D / 8;                         // channels per thread in the merge: 8 threads per row
+  constexpr int RE = D + 16 / (int)sizeof(T);                     // padded LDS row
+  __shared__ __attribute__((aligned(16))) T Ol[32 * RE];
+  const int head = blockIdx.x;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int h = lane / 32, lr = lane % 32;
+  const int HB32 = p.HB * 32;
+  const long ldg = (long)p.nH * D;
+
+  // the first core block of this wave is requested before anything else: the launch is a chain of round trips
+  const T* G = static_cast<const T*>(p.Gtil2) + (long)head * D;
+  Frag<T> gf0[CB];
+  if (wave < p.RT2 / 32) {
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) gf0[cb] = load_frag<T>(G + (long)(wave * 32 + lr) * ldg + cb * 32 + 16 * h);
+  }
+
+  // ---- merged, normalised O_i[tok][c] -> LDS (c stored in acc order inside each 32-block) ----
+  {
+    const int tok = threadIdx.x / 8, c0 = (threadIdx.x % 8) * CPT;
+    float num[CPT];
+#pragma unroll
+    for (int e = 0; e < CPT; ++e) num[e] = 0.f;
+    float mrun = -INFINITY, den = 0.f;
+    if (tok < p.Bsz) {
+      constexpr int U = 16;                                       // splits whose loads are issued together (one
+                                                                  // workgroup per compute unit: registers are plentiful)
+      for (int s0 = 0; s0 < p.nsplit; s0 += U) {
+        float mv[U], lv[U];
+        f32x4 ov[U][CPT / 4];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const long ps = ((long)tok * p.nsplit + min(s0 + u, p.nsplit - 1)) * HB32 + head;
+          mv[u] = p.part_m[ps];
+          lv[u] = p.part_l[ps];
+#pragma unroll
+          for (int q = 0; q < CPT / 4; ++q) ov[u][q] = *reinterpret_cast<const f32x4*>(p.part_o + ps * D + c0 + 4 * q);
+        }
+        float mb = mrun;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (s0 + u < p.nsplit) mb = fmaxf(mb, mv[u]);
+        if (mb == -INFINITY) continue;                            // only empty splits so far
+        const float a = fast_exp2(mrun - mb);                     // 0 while mrun is still -inf
+        den *= a;
+#pragma unroll
+        for (int e = 0; e < CPT; ++e) num[e] *= a;
+        mrun = mb;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const bool live = s0 + u < p.nsplit && mv[u] != -INFINITY;
+          const float w = live ? fast_exp2(mv[u] - mb) : 0.f;
+          den += w * lv[u];
+#pragma unroll
+          for (int q = 0; q < CPT / 4; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) num[4 * q + r] += w * ov[u][q][r];
+        }
+      }
+    }
+    const float inv = tok < p.Bsz ? 1.f / den : 0.f;              // rows past the batch are zero
+#pragma unroll
+    for (int q = 0; q < CPT / 4; ++q) {
+      const int c = c0 + 4 * q;                                   // four consecutive channels keep their order
+      store4(Ol + tok * RE + (c & ~31) + acc_pos(c & 31), num[4 * q] * inv, num[4 * q + 1] * inv, num[4 * q + 2] * inv,
+             num[4 * q + 3] * inv);
+    }
+  }
+  __syncthreads();
+
+  // ---- Zpart_i^T[b][tok]: wave w takes the 32-row blocks w, w+4, ... of the core ----
+  for (int rb = wave; rb < p.RT2 / 32; rb += 4) {
+    Frag<T> gf[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+      gf[cb] = rb == wave ? gf0[cb] : load_frag<T>(G + (long)(rb * 32 + lr) * ldg + cb * 32 + 16 * h);
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) mma32(acc, gf[cb], load_frag<T>(Ol + lr * RE + cb * 32 + 16 * h));
+    if (lr < p.Bsz) {
+      float* dst = p.zpart + ((long)head * p.Bsz + lr) * p.RT2 + rb * 32 + 4 * h;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) store4(dst + 8 * q, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// output projection of a decode step from the per-head contributions: Y = (sum_heads Zpart) U~2^T
+// ---------------------------------------------------------------------------------------
+// One workgroup per 128 output channels.  Every workgroup first sums the heads' contributions
+// ([nH][Bsz][RT2] fp32, a few hundred KB that stay in L2) into Z [Bsz][RT2] in LDS, loads for 16 heads
+// issued together, while its rows of the output factor are already on their way; then each wave multiplies
+// its 32 factor rows by Z.  (The sum over heads is formed in head order by every workgroup alike.)
+template <typename T>
+__global__ __launch_bounds__(256) void decode_out_kernel(DecodeArgs p) {
+  constexpr int PRE = 4;                                          // contraction blocks requested up front
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* Zl = reinterpret_cast<T*>(smem_raw);                         // [32][RT2 + pad]
+  const int RE = p.RT2 + 16 / (int)sizeof(T);
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int h = lane / 32, lr = lane % 32;
+  const int KB = p.RT2 / 32;
+  const int m_row = blockIdx.x * 128 + wave * 32 + lr;            // this lane's factor row
+  const bool row_ok = m_row < p.d_model;
+  const T* urow = static_cast<const T*>(p.Ut2) + (long)(row_ok ? m_row : 0) * p.ut2_ld + 16 * h;
+  Frag<T> uf[PRE];
+#pragma unroll
+  for (int kb = 0; kb < PRE; ++kb) uf[kb] = kb < KB && row_ok ? load_frag<T>(urow + kb * 32) : zero_frag<T>();
+
+  // ---- Z = sum over heads, rounded to T as the stored Z of a prefill is ----
+  {
+    constexpr int U = 16;
+    const int chunks = 32 * (p.RT2 / 4);                          // (sequence, 4 contraction indices)
+    for (int ci = threadIdx.x; ci < chunks; ci += 256) {
+      const int tok = ci / (p.RT2 / 4), k = (ci % (p.RT2 / 4)) * 4;
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+      if (tok < p.Bsz) {
+        for (int h0 = 0; h0 < p.nH; h0 += U) {
+          f32x4 v[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+            v[u] = *reinterpret_cast<const f32x4*>(p.zpart + ((long)min(h0 + u, p.nH - 1) * p.Bsz + tok) * p.RT2 + k);
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+            if (h0 + u < p.nH) sum += v[u];
+        }
+      }
+      store4(Zl + tok * RE + k, sum[0], sum[1], sum[2], sum[3]);
+    }
+  }
+  __syncthreads();
+
+  f32x16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+  for (int kb = 0; kb < PRE; ++kb)
+    if (kb < KB) mma32(acc, uf[kb], load_frag<T>(Zl + lr * RE + kb * 32 + 16 * h));
+  for (int kb = PRE; kb < KB; ++kb) {
+    const Frag<T> u = row_ok ? load_frag<T>(urow + kb * 32) : zero_frag<T>();
+    mma32(acc, u, load_frag<T>(Zl + lr * RE + kb * 32 + 16 * h));
+  }
+  // lane = sequence, rows = output channels 8q+4h+r of this wave's block
+  if (lr < p.Bsz) {
+    T* yrow = static_cast<T*>(p.Y) + (long)lr * p.d_model + blockIdx.x * 128 + wave * 32 + 4 * h;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (blockIdx.x * 128 + wave * 32 + 8 * q + 4 * h < p.d_model)
+        store4(yrow + 8 * q, acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 template <typename T, int D>
 static hipError_t qhat_one(const DecodeArgs& a, hipStream_t s) {
   hipLaunchKernelGGL((decode_qhat_kernel<T, D>), dim3(a.HB * 32), dim3(256), 0, s, a);
@@ -757,6 +924,33 @@ static hipError_t shared_dispatch(const DecodeArgs& a, hipStream_t s) {
 hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s) {
   if (decode_wave_private(dtype, a.r3, a.D, a.shared_kv)) return shared_dispatch(a, s);
   return dtype == 0 ? attn_dispatch<float, 32>(a, s) : attn_dispatch<bf16, 64>(a, s);
+}
+
+template <typename T>
+static hipError_t merge_heads_dispatch(const DecodeArgs& a, hipStream_t s) {
+  switch (a.D) {
+    case 32: hipLaunchKernelGGL((decode_merge_heads_kernel<T, 32>), dim3(a.nH), dim3(256), 0, s, a); break;
+    case 64: hipLaunchKernelGGL((decode_merge_heads_kernel<T, 64>), dim3(a.nH), dim3(256), 0, s, a); break;
+    case 128: hipLaunchKernelGGL((decode_merge_heads_kernel<T, 128>), dim3(a.nH), dim3(256), 0, s, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+hipError_t launch_decode_merge_heads(int dtype, const DecodeArgs& a, hipStream_t s) {
+  return dtype == 0 ? merge_heads_dispatch<float>(a, s) : merge_heads_dispatch<bf16>(a, s);
+}
+
+template <typename T>
+static hipError_t out_one(const DecodeArgs& a, hipStream_t s) {
+  const size_t smem = 32ul * (a.RT2 + 16 / sizeof(T)) * sizeof(T);
+  auto kern = decode_out_kernel<T>;
+  static LdsOnce lds_once;                                       // one per kernel instantiation
+  if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
+  hipLaunchKernelGGL(kern, dim3((a.d_model + 127) / 128), dim3(256), smem, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_decode_out(int dtype, const DecodeArgs& a, hipStream_t s) {
+  return dtype == 0 ? out_one<float>(a, s) : out_one<bf16>(a, s);
 }
 
 hipError_t launch_decode_merge(int dtype, const DecodeArgs& a, hipStream_t s) {

@@ -159,6 +159,13 @@ struct DecodeArgs {
   int rope_ld;
   int Bsz, nH, HB, R2, r3, rt3, D, Lmax, nsplit;
   int shared_kv;       // 1: Kcache holds the unrotated latent, which is also the value; Vcache is null
+  const void* Gtil2;   // [RT2][nH*D] post-softmax head-mixed cores, c in acc order (head merge)
+  float* zpart;        // [nH][Bsz][RT2] per-head contributions to Z, summed by the split-K reduction
+  int RT2;
+  const void* Ut2;     // [d_model][ut2_ld] output factor, k = RT2 contiguous (padded copy where rt2 is no multiple of 32)
+  long ut2_ld;
+  void* Y;             // [Bsz][d_model]
+  int d_model;
   int kv_len[32];
 };
 
@@ -204,5 +211,7 @@ hipError_t launch_core_grad(int dtype, const CoreGradArgs& a, hipStream_t s);
 hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_merge(int dtype, const DecodeArgs& a, hipStream_t s);
+hipError_t launch_decode_merge_heads(int dtype, const DecodeArgs& a, hipStream_t s);
+hipError_t launch_decode_out(int dtype, const DecodeArgs& a, hipStream_t s);
 
 }  // namespace ta
