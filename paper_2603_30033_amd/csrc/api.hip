@@ -426,6 +426,7 @@ int decode_impl(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x,
     g.rope = c->rope; g.rope_ld = f.max_positions; g.pos0 = 0; g.decode = 1;
     for (int b = 0; b < Bc; ++b) g.kv_pos[b] = len[b] - 1;
     g.ksplit = decode_ksplit(g.K); g.part = ws.part;
+    g.defer_reduce = 1;                                           // the query launch sums the partial tiles
     if (launch_gemm(f.dtype, g, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
     rec.after("factor_projection");
 
@@ -436,7 +437,7 @@ int decode_impl(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x,
     d.Bsz = Bc; d.nH = f.n_heads; d.HB = pad32(f.n_heads) / 32; d.R2 = c->R2; d.r3 = f.r3; d.rt3 = f.rt3;
     d.D = c->D; d.Lmax = Lmax; d.nsplit = decode_nsplit(c, Bc, longest); d.shared_kv = f.shared_kv;
     for (int b = 0; b < Bc; ++b) d.kv_len[b] = len[b];
-    if (launch_decode_qhat(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    if (launch_decode_qhat(f.dtype, d, g, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
     rec.after("decode_query");
     if (launch_decode_attn(f.dtype, d, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
     rec.after("decode_attention");

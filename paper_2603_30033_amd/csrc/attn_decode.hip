@@ -9,31 +9,110 @@
 //   decode_merge   log-sum-exp merge of the partials into the normalised O
 #include "common.h"
 #include "params.h"
+#include "epilogue.h"
 
 namespace ta {
 
 // ---------------------------------------------------------------------------------------
 // Qhat^T[c][tok] = sum_b Gt_i[c][b] Qlat[tok][b];  one workgroup per head slot, wave = c-block
 // ---------------------------------------------------------------------------------------
+// The launch also finishes the factor projection, whose product leaves split-K partial tiles
+// ([split][sequence][R2 + D (+ D)] fp32): every head's workgroup sums the Qlat columns of all sequences into
+// LDS itself (a few hundred KB that stay in L2; all loads of a thread issued together), and the workgroups
+// behind the heads' sum one 32-column block of the key or value part each and run the projection's epilogue
+// on it (rotation, cache rows).  With one split the product has run its epilogue already and Qlat is read
+// from where it put it.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_qhat_kernel(DecodeArgs p) {
+__global__ __launch_bounds__(256) void decode_qhat_kernel(DecodeArgs p, GemmArgs g) {
   constexpr int CB = D / 32;
-  const int head = blockIdx.x;                       // 0 .. HB*32-1
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* Ql = reinterpret_cast<T*>(smem_raw);                         // [32][R2 + pad], acc order inside 32-blocks
+  const int RE = p.R2 + 16 / (int)sizeof(T);
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int h = lane / 32, tok = lane % 32;
+  const int n_heads_wg = p.HB * 32;
+  const int Mp = g.R2 + (g.shared_kv ? 1 : 2) * g.D;
+  constexpr int U = 8;                                            // partial tiles whose loads are issued together
+
+  if ((int)blockIdx.x >= n_heads_wg) {                            // ---- a key / value block of the projection
+    if (wave != 0) return;
+    const int m0 = g.R2 + ((int)blockIdx.x - n_heads_wg) * 32;
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    if (tok < p.Bsz) {
+      for (int z0 = 0; z0 < g.ksplit; z0 += U) {
+        f32x4 v[U][4];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const float* src = g.part + ((long)min(z0 + u, g.ksplit - 1) * p.Bsz + tok) * Mp + m0 + 4 * h;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[u][q] = *reinterpret_cast<const f32x4*>(src + 8 * q);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (z0 + u < g.ksplit)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) acc[4 * q + r] += v[u][q][r];
+      }
+    }
+    epilogue_block<T>(g, acc, m0, tok);
+    return;
+  }
+
+  const int head = blockIdx.x;                                    // 0 .. HB*32-1
+  // this wave's first block of core fragments is requested before the sum: the launch is a chain of round trips
+  const int nbb = p.R2 / 32;
+  const T* Gt = static_cast<const T*>(p.Gt) + (long)min(head, p.nH - 1) * D * p.R2;
+  constexpr int PRE = 4;
+  Frag<T> gf0[PRE];
+#pragma unroll
+  for (int bb = 0; bb < PRE; ++bb)
+    gf0[bb] = load_frag_major<T>(Gt + (long)(min(wave, CB - 1) * nbb + min(bb, nbb - 1)) * kFragBlockElems, lane);
+
+  // ---- Qlat [sequence][R2] in the storage type, acc order -> LDS ----
+  for (int ci = threadIdx.x; ci < 32 * (p.R2 / 4); ci += 256) {
+    const int t = ci / (p.R2 / 4), k = (ci % (p.R2 / 4)) * 4;     // four natural indices k..k+3 keep their order
+    const int pos = (k & ~31) + acc_pos(k & 31);
+    if (g.ksplit > 1) {
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+      if (t < p.Bsz) {
+        for (int z0 = 0; z0 < g.ksplit; z0 += 2 * U) {
+          f32x4 v[2 * U];
+#pragma unroll
+          for (int u = 0; u < 2 * U; ++u)
+            v[u] = *reinterpret_cast<const f32x4*>(g.part + ((long)min(z0 + u, g.ksplit - 1) * p.Bsz + t) * Mp + k);
+#pragma unroll
+          for (int u = 0; u < 2 * U; ++u)
+            if (z0 + u < g.ksplit) sum += v[u];
+        }
+      }
+      store4(Ql + t * RE + pos, sum[0], sum[1], sum[2], sum[3]);
+    } else {
+      const T* src = static_cast<const T*>(p.Qlat) + (long)t * p.R2 + pos;   // already in acc order
+      if (t < p.Bsz) store4(Ql + t * RE + pos, to_f32(src[0]), to_f32(src[1]), to_f32(src[2]), to_f32(src[3]));
+      else store4(Ql + t * RE + pos, 0.f, 0.f, 0.f, 0.f);
+    }
+  }
+  __syncthreads();
+
   T* Qh = static_cast<T*>(p.Qh);
   for (int cb = wave; cb < CB; cb += 4) {
     f32x16 acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.f;
     if (head < p.nH) {
-      const T* Gt = static_cast<const T*>(p.Gt) + (long)head * D * p.R2;
-      const T* Ql = static_cast<const T*>(p.Qlat);
-      for (int bb = 0; bb < p.R2 / 32; ++bb) {
-        Frag<T> xq = tok < p.Bsz ? load_frag<T>(Ql + (long)tok * p.R2 + bb * 32 + 16 * h) : zero_frag<T>();
-        Frag<T> gf = load_frag_major<T>(Gt + (long)(cb * (p.R2 / 32) + bb) * kFragBlockElems, lane);
-        mma32(acc, gf, xq);
-      }
+#pragma unroll
+      for (int bb = 0; bb < PRE; ++bb)
+        if (bb < nbb) {
+          const Frag<T> gf = cb == wave ? gf0[bb] : load_frag_major<T>(Gt + (long)(cb * nbb + bb) * kFragBlockElems, lane);
+          mma32(acc, gf, load_frag<T>(Ql + tok * RE + bb * 32 + 16 * h));
+        }
+      for (int bb = PRE; bb < nbb; ++bb)
+        mma32(acc, load_frag_major<T>(Gt + (long)(cb * nbb + bb) * kFragBlockElems, lane),
+              load_frag<T>(Ql + tok * RE + bb * 32 + 16 * h));
       if (p.rope != nullptr && tok < p.Bsz) {
         const f32x4* tab = reinterpret_cast<const f32x4*>(p.rope) + (long)(cb * 8 + h) * p.rope_ld + (p.kv_len[tok] - 1);
         f32x4 cs[4];
@@ -840,22 +919,28 @@ __global__ __launch_bounds__(256) void decode_out_kernel(DecodeArgs p) {
 
 // ---------------------------------------------------------------------------------------
 template <typename T, int D>
-static hipError_t qhat_one(const DecodeArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL((decode_qhat_kernel<T, D>), dim3(a.HB * 32), dim3(256), 0, s, a);
+static hipError_t qhat_one(const DecodeArgs& a, const GemmArgs& proj, hipStream_t s) {
+  const size_t smem = 32ul * (a.R2 + 16 / sizeof(T)) * sizeof(T);
+  auto kern = decode_qhat_kernel<T, D>;
+  static LdsOnce lds_once;                                       // one per kernel instantiation
+  if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
+  // behind the heads' workgroups: one per 32-column block of the projection's key (and value) part
+  const int kv_blocks = proj.ksplit > 1 ? (proj.shared_kv ? 1 : 2) * proj.D / 32 : 0;
+  hipLaunchKernelGGL(kern, dim3(a.HB * 32 + kv_blocks), dim3(256), smem, s, a, proj);
   return hipGetLastError();
 }
-hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, hipStream_t s) {
+hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, const GemmArgs& proj, hipStream_t s) {
   if (dtype == 0) {
     switch (a.D) {
-      case 32: return qhat_one<float, 32>(a, s);
-      case 64: return qhat_one<float, 64>(a, s);
-      case 128: return qhat_one<float, 128>(a, s);
+      case 32: return qhat_one<float, 32>(a, proj, s);
+      case 64: return qhat_one<float, 64>(a, proj, s);
+      case 128: return qhat_one<float, 128>(a, proj, s);
     }
   } else {
     switch (a.D) {
-      case 32: return qhat_one<bf16, 32>(a, s);
-      case 64: return qhat_one<bf16, 64>(a, s);
-      case 128: return qhat_one<bf16, 128>(a, s);
+      case 32: return qhat_one<bf16, 32>(a, proj, s);
+      case 64: return qhat_one<bf16, 64>(a, proj, s);
+      case 128: return qhat_one<bf16, 128>(a, proj, s);
     }
   }
   return hipErrorInvalidValue;

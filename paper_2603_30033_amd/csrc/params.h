@@ -71,6 +71,7 @@ struct GemmArgs {
   // epilogue
   int ksplit;
   float* part;
+  int defer_reduce;     // 1: no reduction launch here; the caller's next kernel sums the partial tiles
   // epi 3: out_scale * acc[m][n] as fp32; column range [n0, n1) of the product goes to
   // ptr[m * ld + (n - n0)] (up to three destinations; ptr null = unused)
   struct Out3 { float* ptr; int n0, n1; long ld; } out3[3];
@@ -208,7 +209,7 @@ hipError_t launch_bwd_dq(int dtype, const BwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_dkv(int dtype, const BwdArgs& a, hipStream_t s);
 hipError_t launch_kv_reduce(int dtype, const KvReduceArgs& a, hipStream_t s);
 hipError_t launch_core_grad(int dtype, const CoreGradArgs& a, hipStream_t s);
-hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, hipStream_t s);
+hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, const GemmArgs& proj, hipStream_t s);
 hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_merge(int dtype, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_merge_heads(int dtype, const DecodeArgs& a, hipStream_t s);
