@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtucker_attn.so")
 SOURCES = ["api.hip", "prep.hip", "gemm.hip", "out_proj.hip", "attn_prefill.hip", "attn_decode.hip",
-           "attn_bwd.hip", "gemm_tn.hip", "bwd_misc.hip", "convert.hip", "ceiling.hip"]
+           "attn_bwd.hip", "gemm_tn.hip", "bwd_misc.hip", "convert.hip", "ceiling.hip", "decode_proj.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed fp32 instructions are kept off: scalar fp32 code must not be fused into them
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

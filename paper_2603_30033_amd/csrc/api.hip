@@ -221,6 +221,13 @@ int decode_ksplit(int K) {
   int nk = (K + 63) / 64;
   return nk < 16 ? (nk < 1 ? 1 : nk) : 16;
 }
+// the decode projection can read the factor matrices as they lie in memory when every row of them is a whole
+// number of aligned 16-byte chunks
+bool decode_direct_projection(const tucker_attn_ctx* c, const tucker_attn_weights* w) {
+  const tucker_attn_config& f = c->cfg;
+  auto chunked = [&](const void* p, int r) { return reinterpret_cast<uintptr_t>(p) % 16 == 0 && (r * c->es) % 16 == 0; };
+  return chunked(w->U2, f.r2) && chunked(w->U3, f.r3) && (f.shared_kv || chunked(w->Ut3, f.rt3));
+}
 
 DecodeWs carve_decode(const tucker_attn_ctx* c, void* ws, int B) {
   const tucker_attn_config& f = c->cfg;
@@ -236,7 +243,8 @@ DecodeWs carve_decode(const tucker_attn_ctx* c, void* ws, int B) {
   w.pm = cv.take<float>((size_t)B * ns * HB32 * 4);
   w.pl = cv.take<float>((size_t)B * ns * HB32 * 4);
   w.po = cv.take<float>((size_t)B * ns * HB32 * c->D * 4);
-  const size_t p1 = (size_t)decode_ksplit(f.d_model) * B * (c->R2 + 2 * c->D) * 4;
+  const int ks1 = decode_ksplit(f.d_model) < 2 ? 2 : decode_ksplit(f.d_model);
+  const size_t p1 = (size_t)ks1 * B * (c->R2 + 2 * c->D) * 4;
   const size_t p2 = (size_t)f.n_heads * B * c->RT2 * 4;            // one contribution to Z per head
   w.part = cv.take<float>(p1 > p2 ? p1 : p2);
   w.bytes = cv.off;
@@ -257,7 +265,7 @@ void add_job(PrepArgs& pa, const void* src, const void* coef, void* out, int A, 
 
 // head-mixed cores and factor matrices in MFMA operand layout; returns the output-factor pointer
 PrepArgs make_prep(const tucker_attn_ctx* c, const tucker_attn_weights* w, void* Gt, void* Gtil2, void* Wcat,
-                   void* Ut2p, const void** ut2_used, long* ut2_ld) {
+                   void* Ut2p, const void** ut2_used, long* ut2_ld, bool with_wcat = true) {
   const tucker_attn_config& f = c->cfg;
   const int es = c->es;
   PrepArgs pa;
@@ -269,11 +277,13 @@ PrepArgs make_prep(const tucker_attn_ctx* c, const tucker_attn_weights* w, void*
   add_job(pa, w->Ct, w->Ut1, Gtil2, f.rt1, f.rt2, f.rt3, f.n_heads, c->RT2, c->D, c->D, nHD, 0, 1, 1.f);
   // Wcat rows: U2^T | U3^T | U~3^T, each [rank_pad][dp]
   char* wc = static_cast<char*>(Wcat);
-  add_job(pa, w->U2, nullptr, wc, 1, f.d_model, f.r2, 1, c->dp, c->R2, 0, c->dp, 1, 0, 1.f);
-  add_job(pa, w->U3, nullptr, wc + (size_t)c->R2 * c->dp * es, 1, f.d_model, f.r3, 1, c->dp, c->D, 0, c->dp, 1, 0, 1.f);
-  if (!f.shared_kv)
-    add_job(pa, w->Ut3, nullptr, wc + (size_t)(c->R2 + c->D) * c->dp * es, 1, f.d_model, f.rt3, 1, c->dp, c->D, 0,
-            c->dp, 1, 0, 1.f);
+  if (with_wcat) {
+    add_job(pa, w->U2, nullptr, wc, 1, f.d_model, f.r2, 1, c->dp, c->R2, 0, c->dp, 1, 0, 1.f);
+    add_job(pa, w->U3, nullptr, wc + (size_t)c->R2 * c->dp * es, 1, f.d_model, f.r3, 1, c->dp, c->D, 0, c->dp, 1, 0, 1.f);
+    if (!f.shared_kv)
+      add_job(pa, w->Ut3, nullptr, wc + (size_t)(c->R2 + c->D) * c->dp * es, 1, f.d_model, f.rt3, 1, c->dp, c->D, 0,
+              c->dp, 1, 0, 1.f);
+  }
   if (f.rt2 != c->RT2) {
     add_job(pa, w->Ut2, nullptr, Ut2p, 1, f.d_model, f.rt2, 1, c->dp, c->RT2, 0, c->RT2, 0, 0, 1.f);
     *ut2_used = Ut2p;
@@ -407,15 +417,19 @@ int decode_impl(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x,
     int longest = 1;
     for (int b = 0; b < Bc; ++b) longest = len[b] > longest ? len[b] : longest;
 
+    // Factor matrices whose rows are whole 16-byte chunks are multiplied as they lie in memory, in a launch that
+    // also carries the weight-preparation tiles; other shapes go through transposed copies and the product kernel.
+    const bool direct = decode_direct_projection(c, w);
     const void* ut2;
     long ut2_ld;
-    PrepArgs pa = make_prep(c, w, ws.Gt, ws.Gtil2, ws.Wcat, ws.Ut2p, &ut2, &ut2_ld);
-    if (!c->prepared && b0 == 0) {
+    PrepArgs pa = make_prep(c, w, ws.Gt, ws.Gtil2, ws.Wcat, ws.Ut2p, &ut2, &ut2_ld, !direct);
+    const bool prepare_now = !c->prepared && b0 == 0;
+    if (prepare_now && !direct) {
       if (launch_prep(f.dtype, pa, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
       rec.after("prep_weights");
     }
 
-    GemmArgs g;
+    GemmArgs g;                                                   // the projection's epilogue and partial-tile layout
     std::memset(&g, 0, sizeof(g));
     g.A = ws.Wcat; g.lda = c->dp; g.M = c->R2 + (f.shared_kv ? 1 : 2) * c->D; g.shared_kv = f.shared_kv;
     g.Bsrc = xb; g.ldb = f.d_model; g.K = f.d_model;
@@ -427,7 +441,19 @@ int decode_impl(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x,
     for (int b = 0; b < Bc; ++b) g.kv_pos[b] = len[b] - 1;
     g.ksplit = decode_ksplit(g.K); g.part = ws.part;
     g.defer_reduce = 1;                                           // the query launch sums the partial tiles
-    if (launch_gemm(f.dtype, g, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    if (direct) {
+      if (g.ksplit < 2) g.ksplit = 2;                             // always partial tiles on this path
+      DecodeProjArgs dp;
+      std::memset(&dp, 0, sizeof(dp));
+      dp.X = xb; dp.U2 = w->U2; dp.U3 = w->U3; dp.Ut3 = w->Ut3;
+      dp.r2 = f.r2; dp.r3 = f.r3; dp.rt3 = f.rt3; dp.R2 = c->R2; dp.D = c->D;
+      dp.K = f.d_model; dp.Bsz = Bc; dp.ksplit = g.ksplit; dp.shared_kv = f.shared_kv; dp.part = ws.part;
+      PrepArgs none;
+      std::memset(&none, 0, sizeof(none));
+      if (launch_decode_proj(f.dtype, dp, prepare_now ? pa : none, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    } else {
+      if (launch_gemm(f.dtype, g, 32, s) != hipSuccess) return TUCKER_ATTN_HIP_ERROR;
+    }
     rec.after("factor_projection");
 
     DecodeArgs d;

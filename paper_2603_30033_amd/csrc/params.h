@@ -209,6 +209,21 @@ hipError_t launch_bwd_dq(int dtype, const BwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_dkv(int dtype, const BwdArgs& a, hipStream_t s);
 hipError_t launch_kv_reduce(int dtype, const KvReduceArgs& a, hipStream_t s);
 hipError_t launch_core_grad(int dtype, const CoreGradArgs& a, hipStream_t s);
+// Factor projection of a decode step straight from the caller's factor matrices (no transposed copies):
+// rows [0,R2) of the product are Qlat, [R2,R2+D) the key latent, [R2+D,R2+2D) the value latent; it leaves
+// split-K partial tiles for the query launch to sum.  Needs factor rows that are whole 16-byte chunks.
+struct DecodeProjArgs {
+  const void* X;        // [Bsz][K]
+  const void* U2;       // [K][r2]
+  const void* U3;       // [K][r3]
+  const void* Ut3;      // [K][rt3]; unused for a shared latent
+  int r2, r3, rt3;
+  int R2, D;
+  int K, Bsz, ksplit, shared_kv;
+  float* part;          // [ksplit][Bsz][Mp] fp32, Mp = R2 + (shared_kv ? 1 : 2) * D
+};
+// `prep` (possibly empty): weight-preparation tiles that ride along as the first workgroups of the launch
+hipError_t launch_decode_proj(int dtype, const DecodeProjArgs& a, const PrepArgs& prep, hipStream_t s);
 hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, const GemmArgs& proj, hipStream_t s);
 hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_merge(int dtype, const DecodeArgs& a, hipStream_t s);
