@@ -86,7 +86,7 @@ struct PrefillWs {
   size_t bytes;
 };
 struct DecodeWs {
-  void *Gt, *Gtil2, *Wcat, *Ut2p, *Qlat, *Qh, *O, *Z;
+  void *Gt, *Gtil2, *Wcat, *Ut2p, *Qlat, *Qh;
   float *pm, *pl, *po, *part;
   size_t bytes;
 };
@@ -238,8 +238,6 @@ DecodeWs carve_decode(const tucker_attn_ctx* c, void* ws, int B) {
   carve_weights(c, cv, w.Gt, w.Gtil2, w.Wcat, w.Ut2p);
   w.Qlat = cv.take<char>((size_t)32 * c->R2 * c->es);
   w.Qh = cv.take<char>((size_t)B * HB32 * c->D * c->es);
-  w.O = cv.take<char>((size_t)B * f.n_heads * c->D * c->es);
-  w.Z = cv.take<char>((size_t)B * c->RT2 * c->es);
   w.pm = cv.take<float>((size_t)B * ns * HB32 * 4);
   w.pl = cv.take<float>((size_t)B * ns * HB32 * 4);
   w.po = cv.take<float>((size_t)B * ns * HB32 * c->D * 4);
@@ -459,7 +457,7 @@ int decode_impl(tucker_attn_ctx* c, const tucker_attn_weights* w, const void* x,
     DecodeArgs d;
     std::memset(&d, 0, sizeof(d));
     d.Qlat = ws.Qlat; d.Gt = ws.Gt; d.Qh = ws.Qh; d.Kcache = Kb; d.Vcache = Vb;
-    d.part_m = ws.pm; d.part_l = ws.pl; d.part_o = ws.po; d.O = ws.O; d.rope = c->rope; d.rope_ld = f.max_positions;
+    d.part_m = ws.pm; d.part_l = ws.pl; d.part_o = ws.po; d.rope = c->rope; d.rope_ld = f.max_positions;
     d.Bsz = Bc; d.nH = f.n_heads; d.HB = pad32(f.n_heads) / 32; d.R2 = c->R2; d.r3 = f.r3; d.rt3 = f.rt3;
     d.D = c->D; d.Lmax = Lmax; d.nsplit = decode_nsplit(c, Bc, longest); d.shared_kv = f.shared_kv;
     for (int b = 0; b < Bc; ++b) d.kv_len[b] = len[b];

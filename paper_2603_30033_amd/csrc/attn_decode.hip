@@ -6,7 +6,8 @@
 //   decode_qhat    Qhat_i = qscale * Qlat G_i, latent RoPE at position kv_len-1
 //   decode_attn    split-KV: each workgroup streams a contiguous slice of one sequence's
 //                  cache through LDS once and emits a partial (max, sum, O) per head
-//   decode_merge   log-sum-exp merge of the partials into the normalised O
+//   decode_merge_heads  log-sum-exp merge of the partials and the head merge, one workgroup per head
+//   decode_out     output projection from the heads' contributions
 #include "common.h"
 #include "params.h"
 #include "epilogue.h"
@@ -705,56 +706,10 @@ void decode_attn_shared_kernel(DecodeArgs p) {
 }
 
 // ---------------------------------------------------------------------------------------
-// merge of split partials -> O[b][head][c] (c stored in acc order for the latent merge GEMM)
-// ---------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs p) {
-  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-  const long total = (long)p.Bsz * p.nH * p.D;
-  if (idx >= total) return;
-  const int c = idx % p.D;
-  const int head = (idx / p.D) % p.nH;
-  const int b = idx / ((long)p.D * p.nH);
-  const int HB32 = p.HB * 32;
-  // one pass over the splits in batches of 8 whose loads are all issued before the first use;
-  // the running maximum is carried as in the attention kernel itself
-  constexpr int U = 8;
-  float mrun = -INFINITY, num = 0.f, den = 0.f;
-  for (int s0 = 0; s0 < p.nsplit; s0 += U) {
-    float mv[U], lv[U], ov[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const long ps = ((long)b * p.nsplit + min(s0 + u, p.nsplit - 1)) * HB32 + head;
-      mv[u] = p.part_m[ps];
-      lv[u] = p.part_l[ps];
-      ov[u] = p.part_o[ps * p.D + c];
-    }
-    float mb = mrun;
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (s0 + u < p.nsplit) mb = fmaxf(mb, mv[u]);
-    if (mb == -INFINITY) continue;                                // only empty splits so far
-    const float a = fast_exp2(mrun - mb);                         // 0 while mrun is still -inf
-    num *= a;
-    den *= a;
-    mrun = mb;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const bool live = s0 + u < p.nsplit && mv[u] != -INFINITY;  // beyond the end, or an empty split
-      const float w = live ? fast_exp2(mv[u] - mb) : 0.f;
-      den += w * lv[u];
-      num += w * ov[u];
-    }
-  }
-  T* O = static_cast<T*>(p.O);
-  store1(O + ((long)b * p.nH + head) * p.D + (c & ~31) + acc_pos(c & 31), num / den);
-}
-
-// ---------------------------------------------------------------------------------------
 // merge of split partials and head merge in one launch: one workgroup per head
 // ---------------------------------------------------------------------------------------
-// The workgroup of head i merges the split partials of its head for every sequence (as decode_merge
-// does), keeps the normalised O_i [sequence][c] in LDS in operand order, and multiplies it by the head's
+// The workgroup of head i merges the split partials of its head for every sequence (log-sum-exp, loads
+// of 16 splits issued together), keeps the normalised O_i [sequence][c] in LDS in operand order, and multiplies it by the head's
 // post-softmax core: Zpart_i^T[b][sequence] = sum_c G~_i[b][c] O_i[sequence][c].  The per-head
 // contributions are written where a split-K product would put its partial tiles ([head][sequence][RT2],
 // fp32), and the split-K reduction sums them over heads into Z.  This replaces two launches (the merge and
@@ -1036,16 +991,6 @@ static hipError_t out_one(const DecodeArgs& a, hipStream_t s) {
 }
 hipError_t launch_decode_out(int dtype, const DecodeArgs& a, hipStream_t s) {
   return dtype == 0 ? out_one<float>(a, s) : out_one<bf16>(a, s);
-}
-
-hipError_t launch_decode_merge(int dtype, const DecodeArgs& a, hipStream_t s) {
-  const long total = (long)a.Bsz * a.nH * a.D;
-  const int blocks = (int)((total + 255) / 256);
-  if (dtype == 0)
-    hipLaunchKernelGGL(decode_merge_kernel<float>, dim3(blocks), dim3(256), 0, s, a);
-  else
-    hipLaunchKernelGGL(decode_merge_kernel<bf16>, dim3(blocks), dim3(256), 0, s, a);
-  return hipGetLastError();
 }
 
 }  // namespace ta

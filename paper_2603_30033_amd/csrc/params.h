@@ -155,7 +155,6 @@ struct DecodeArgs {
   float* part_m;       // [B][nsplit][HB*32]
   float* part_l;
   float* part_o;       // [B][nsplit][HB*32][D]
-  void* O;             // [32][nH][D] acc order in c (rows >= B zero)
   const float4* rope; // [D/4][rope_ld] as in GemmArgs, or null
   int rope_ld;
   int Bsz, nH, HB, R2, r3, rt3, D, Lmax, nsplit;
@@ -226,7 +225,6 @@ struct DecodeProjArgs {
 hipError_t launch_decode_proj(int dtype, const DecodeProjArgs& a, const PrepArgs& prep, hipStream_t s);
 hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, const GemmArgs& proj, hipStream_t s);
 hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s);
-hipError_t launch_decode_merge(int dtype, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_merge_heads(int dtype, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_out(int dtype, const DecodeArgs& a, hipStream_t s);
 
