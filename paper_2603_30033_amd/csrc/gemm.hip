@@ -352,10 +352,16 @@ hipError_t launch_gemm(int dtype, const GemmArgs& a, int tile_n, hipStream_t s) 
   // every compute unit two workgroups)
   if (tile_n == 64 && m_rows > 128 && m_rows <= 192 && ((long)a.Bsz * a.Npad + 63) / 64 >= 512)
     return launch_one<bf16, 192, 64, 2, 2>(a, m_rows, s);
-  // An odd number of 128-row tiles that is a whole number of 192-row tiles (384 rows: query, key and value
-  // factors of 128 each): 192-row tiles give an even workgroup count (256 instead of 384 at 8192 tokens, one per
-  // compute unit instead of one and a half) and 13 % fewer bytes from L2 into LDS; 49.4 against 51.9 us there
-  if (tile_n == 64 && m_rows % 192 == 0 && (m_rows / 128) % 2 == 1) return launch_one<bf16, 192, 64, 2, 2>(a, m_rows, s);
+  // An odd number of 128-row tiles that is a whole number of 96-row tiles (384 rows: query, key and value
+  // factors of 128 each) leaves the compute units one and a half workgroups each.  96 x 128 tiles (every wave
+  // 96 rows x 32 tokens) give 256 equal workgroups at 8192 tokens and move 224 instead of 256 (192 x 64 tiles)
+  // or 288 (128 x 64) rows through LDS per 12288 outputs: 50.0 us against 53.9 (192 x 64) and 56 (128 x 64),
+  // event-bracketed.  With fewer tokens than fill the chip that way, 192-row tiles still even out the count.
+  if (tile_n == 64 && m_rows % 96 == 0 && (m_rows / 128) % 2 == 1) {
+    const long tokens = (long)a.Bsz * a.Npad;
+    if ((m_rows / 96) * ((tokens + 127) / 128) >= 256) return launch_one<bf16, 96, 128, 1, 4>(a, m_rows, s);
+    if (m_rows % 192 == 0) return launch_one<bf16, 192, 64, 2, 2>(a, m_rows, s);
+  }
   if (tile_n >= 128) return launch_one<bf16, 128, 128, 2, 2>(a, m_rows, s);
   if (tile_n >= 64) return launch_one<bf16, 128, 64, 2, 2>(a, m_rows, s);
   return launch_one<bf16, 128, 32, 4, 1>(a, m_rows, s);
