@@ -255,11 +255,14 @@ int tucker_attn_release_weights(tucker_attn_ctx *ctx);
  * Optional per-kernel timing for benchmarks.  While enabled, forward/backward/decode bracket every
  * kernel they launch with HIP events recorded on the caller's stream; tucker_attn_profile_read
  * synchronises those events and returns, for the LAST call, the kernel count and for each
- * kernel its name and duration.  Event recording perturbs end-to-end time slightly, so
- * throughput is measured with profiling disabled.
+ * kernel its name and duration (the time between the two events around the launch, which includes
+ * the dispatch on either side).  For the attention launch of a forward or decode call one more entry
+ * follows the kernels: "attention_kernel" / "decode_attention_kernel", the duration of that kernel
+ * alone, from a start and a stop event attached to its dispatch.  Event recording perturbs
+ * end-to-end time slightly, so throughput is measured with profiling disabled.
  *   names   host array of n_max pointers, receives static strings (nullable)
  *   ms      host array of n_max floats (nullable)
- * Returns the number of kernels of the last call (<= 40) or a negative status.
+ * Returns the number of entries of the last call (<= 41) or a negative status.
  */
 int tucker_attn_profile_enable(tucker_attn_ctx *ctx, int32_t on);
 int tucker_attn_profile_read(tucker_attn_ctx *ctx, const char **names, float *ms, int32_t n_max);

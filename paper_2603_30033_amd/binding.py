@@ -292,9 +292,9 @@ def tucker_attn_profile_enable(ctx: int, on: bool) -> None:
 
 
 def tucker_attn_profile_read(ctx: int) -> List[Tuple[str, float]]:
-    names = (C.c_char_p * 40)()
-    ms = (C.c_float * 40)()
-    n = load_library().tucker_attn_profile_read(ctx, names, ms, 40)
+    names = (C.c_char_p * 41)()
+    ms = (C.c_float * 41)()
+    n = load_library().tucker_attn_profile_read(ctx, names, ms, 41)
     if n < 0:
         _check(n, "tucker_attn_profile_read")
     return [(names[i].decode(), float(ms[i])) for i in range(n)]

@@ -902,68 +902,70 @@ hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, const GemmArgs& pr
 }
 
 template <typename T, int D, int BC, int HB, bool SH>
-static hipError_t attn_one_sh(const DecodeArgs& a, hipStream_t s) {
+static hipError_t attn_one_sh(const DecodeArgs& a, hipStream_t s, hipEvent_t k0, hipEvent_t k1) {
   size_t smem = DecLds<T, D, BC>::kBytes;
   auto kern = decode_attn_kernel<T, D, BC, HB, SH>;
   static LdsOnce lds_once;                                       // one per kernel instantiation
   if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
-  hipLaunchKernelGGL(kern, dim3(a.nsplit, a.Bsz), dim3(256), smem, s, a);
+  if (k0 != nullptr && k1 != nullptr) hipExtLaunchKernelGGL(kern, dim3(a.nsplit, a.Bsz), dim3(256), (uint32_t)smem, s, k0, k1, 0, a);
+  else hipLaunchKernelGGL(kern, dim3(a.nsplit, a.Bsz), dim3(256), smem, s, a);
   return hipGetLastError();
 }
 template <typename T, int D, int BC, int HB>
-static hipError_t attn_one(const DecodeArgs& a, hipStream_t s) {
-  return a.shared_kv ? attn_one_sh<T, D, BC, HB, true>(a, s) : attn_one_sh<T, D, BC, HB, false>(a, s);
+static hipError_t attn_one(const DecodeArgs& a, hipStream_t s, hipEvent_t k0, hipEvent_t k1) {
+  return a.shared_kv ? attn_one_sh<T, D, BC, HB, true>(a, s, k0, k1) : attn_one_sh<T, D, BC, HB, false>(a, s, k0, k1);
 }
 template <typename T, int BC>
-static hipError_t attn_dispatch(const DecodeArgs& a, hipStream_t s) {
+static hipError_t attn_dispatch(const DecodeArgs& a, hipStream_t s, hipEvent_t k0, hipEvent_t k1) {
   if (a.HB == 1) {
     switch (a.D) {
-      case 32: return attn_one<T, 32, BC, 1>(a, s);
-      case 64: return attn_one<T, 64, BC, 1>(a, s);
-      case 128: return attn_one<T, 128, BC, 1>(a, s);
+      case 32: return attn_one<T, 32, BC, 1>(a, s, k0, k1);
+      case 64: return attn_one<T, 64, BC, 1>(a, s, k0, k1);
+      case 128: return attn_one<T, 128, BC, 1>(a, s, k0, k1);
     }
   } else if (a.HB == 2) {
     switch (a.D) {
-      case 32: return attn_one<T, 32, BC, 2>(a, s);
-      case 64: return attn_one<T, 64, BC, 2>(a, s);
-      case 128: return attn_one<T, 128, BC, 2>(a, s);
+      case 32: return attn_one<T, 32, BC, 2>(a, s, k0, k1);
+      case 64: return attn_one<T, 64, BC, 2>(a, s, k0, k1);
+      case 128: return attn_one<T, 128, BC, 2>(a, s, k0, k1);
     }
   }
   return hipErrorInvalidValue;
 }
 template <int D, int HB, bool ROT>
-static hipError_t shared_one(const DecodeArgs& a, hipStream_t s) {
+static hipError_t shared_one(const DecodeArgs& a, hipStream_t s, hipEvent_t k0, hipEvent_t k1) {
   const size_t smem = DecWaveLds<D, ROT>::bytes(HB);
   auto kern = decode_attn_shared_kernel<D, HB, ROT>;
   static LdsOnce lds_once;                                       // one per kernel instantiation
   if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
-  hipLaunchKernelGGL(kern, dim3(a.nsplit, a.Bsz), dim3(256), smem, s, a);
+  if (k0 != nullptr && k1 != nullptr) hipExtLaunchKernelGGL(kern, dim3(a.nsplit, a.Bsz), dim3(256), (uint32_t)smem, s, k0, k1, 0, a);
+  else hipLaunchKernelGGL(kern, dim3(a.nsplit, a.Bsz), dim3(256), smem, s, a);
   return hipGetLastError();
 }
 template <int D, int HB>
-static hipError_t shared_variant(const DecodeArgs& a, hipStream_t s) {
-  return a.rope != nullptr ? shared_one<D, HB, true>(a, s) : shared_one<D, HB, false>(a, s);
+static hipError_t shared_variant(const DecodeArgs& a, hipStream_t s, hipEvent_t k0, hipEvent_t k1) {
+  return a.rope != nullptr ? shared_one<D, HB, true>(a, s, k0, k1) : shared_one<D, HB, false>(a, s, k0, k1);
 }
-static hipError_t shared_dispatch(const DecodeArgs& a, hipStream_t s) {
+static hipError_t shared_dispatch(const DecodeArgs& a, hipStream_t s, hipEvent_t k0, hipEvent_t k1) {
   if (a.HB == 1) {
     switch (a.D) {
-      case 32: return shared_variant<32, 1>(a, s);
-      case 64: return shared_variant<64, 1>(a, s);
-      case 128: return shared_variant<128, 1>(a, s);
+      case 32: return shared_variant<32, 1>(a, s, k0, k1);
+      case 64: return shared_variant<64, 1>(a, s, k0, k1);
+      case 128: return shared_variant<128, 1>(a, s, k0, k1);
     }
   } else if (a.HB == 2) {
     switch (a.D) {
-      case 32: return shared_variant<32, 2>(a, s);
-      case 64: return shared_variant<64, 2>(a, s);
-      case 128: return shared_variant<128, 2>(a, s);
+      case 32: return shared_variant<32, 2>(a, s, k0, k1);
+      case 64: return shared_variant<64, 2>(a, s, k0, k1);
+      case 128: return shared_variant<128, 2>(a, s, k0, k1);
     }
   }
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s) {
-  if (decode_wave_private(dtype, a.r3, a.D, a.shared_kv)) return shared_dispatch(a, s);
-  return dtype == 0 ? attn_dispatch<float, 32>(a, s) : attn_dispatch<bf16, 64>(a, s);
+hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s, hipEvent_t k0, hipEvent_t k1) {
+  if (decode_wave_private(dtype, a.r3, a.D, a.shared_kv)) return shared_dispatch(a, s, k0, k1);
+  return dtype == 0 ? attn_dispatch<float, 32>(a, s, k0, k1) : attn_dispatch<bf16, 64>(a, s, k0, k1);
 }
 
 template <typename T>

@@ -398,29 +398,30 @@ __global__ __launch_bounds__(64 * QW * HW) void attn_prefill_kernel(AttnArgs p) 
 }
 
 template <typename T, int D, int QB, int BC, int QW, int HW>
-static hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
+static hipError_t launch_one(const AttnArgs& a, hipStream_t s, hipEvent_t k0, hipEvent_t k1) {
   constexpr int TQ = 32 * QB * QW;
   dim3 grid(((a.nH + HW - 1) / HW) * a.Bsz, (a.N + TQ - 1) / TQ);
   size_t smem = AttnLds<T, D, BC>::kBytes;
   auto kern = attn_prefill_kernel<T, D, QB, BC, QW, HW>;
   static LdsOnce lds_once;                                       // one per kernel instantiation
   if (hipError_t ae = allow_dynamic_lds(lds_once, kern, smem); ae != hipSuccess) return ae;
-  hipLaunchKernelGGL(kern, grid, dim3(64 * QW * HW), smem, s, a);
+  if (k0 != nullptr && k1 != nullptr) hipExtLaunchKernelGGL(kern, grid, dim3(64 * QW * HW), (uint32_t)smem, s, k0, k1, 0, a);
+  else hipLaunchKernelGGL(kern, grid, dim3(64 * QW * HW), smem, s, a);
   return hipGetLastError();
 }
 
-hipError_t launch_attn_prefill(int dtype, const AttnArgs& a, hipStream_t s) {
+hipError_t launch_attn_prefill(int dtype, const AttnArgs& a, hipStream_t s, hipEvent_t k0, hipEvent_t k1) {
   if (dtype == 0) {
     switch (a.D) {
-      case 32: return launch_one<float, 32, 1, 32, 2, 4>(a, s);
-      case 64: return launch_one<float, 64, 1, 32, 2, 4>(a, s);
-      case 128: return launch_one<float, 128, 1, 32, 2, 4>(a, s);
+      case 32: return launch_one<float, 32, 1, 32, 2, 4>(a, s, k0, k1);
+      case 64: return launch_one<float, 64, 1, 32, 2, 4>(a, s, k0, k1);
+      case 128: return launch_one<float, 128, 1, 32, 2, 4>(a, s, k0, k1);
     }
   } else {
     switch (a.D) {
-      case 32: return launch_one<bf16, 32, 1, 64, 2, 4>(a, s);
-      case 64: return launch_one<bf16, 64, 1, 64, 2, 4>(a, s);
-      case 128: return launch_one<bf16, 128, 1, 64, 2, 4>(a, s);
+      case 32: return launch_one<bf16, 32, 1, 64, 2, 4>(a, s, k0, k1);
+      case 64: return launch_one<bf16, 64, 1, 64, 2, 4>(a, s, k0, k1);
+      case 128: return launch_one<bf16, 128, 1, 64, 2, 4>(a, s, k0, k1);
     }
   }
   return hipErrorInvalidValue;

@@ -3,6 +3,7 @@
 // says bytes.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include <atomic>
@@ -203,7 +204,8 @@ hipError_t launch_out_proj(int dtype, const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm(int dtype, const GemmArgs& a, int tile_n, hipStream_t s);
 hipError_t launch_splitk_reduce(int dtype, const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_tn(int dtype, const TnArgs& a, hipStream_t s);
-hipError_t launch_attn_prefill(int dtype, const AttnArgs& a, hipStream_t s);
+// k0, k1 (both or neither): events that take the start and the end of the kernel itself (profiling)
+hipError_t launch_attn_prefill(int dtype, const AttnArgs& a, hipStream_t s, hipEvent_t k0 = nullptr, hipEvent_t k1 = nullptr);
 hipError_t launch_bwd_dq(int dtype, const BwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_dkv(int dtype, const BwdArgs& a, hipStream_t s);
 hipError_t launch_kv_reduce(int dtype, const KvReduceArgs& a, hipStream_t s);
@@ -224,7 +226,7 @@ struct DecodeProjArgs {
 // `prep` (possibly empty): weight-preparation tiles that ride along as the first workgroups of the launch
 hipError_t launch_decode_proj(int dtype, const DecodeProjArgs& a, const PrepArgs& prep, hipStream_t s);
 hipError_t launch_decode_qhat(int dtype, const DecodeArgs& a, const GemmArgs& proj, hipStream_t s);
-hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s);
+hipError_t launch_decode_attn(int dtype, const DecodeArgs& a, hipStream_t s, hipEvent_t k0 = nullptr, hipEvent_t k1 = nullptr);
 hipError_t launch_decode_merge_heads(int dtype, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_out(int dtype, const DecodeArgs& a, hipStream_t s);
 
