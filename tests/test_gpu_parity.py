@@ -609,3 +609,52 @@ def test_forward_replays_correctly_from_a_hip_graph():
             torch.cuda.synchronize()
             assert np.array_equal(got, to_host(Ye)), f"replay {rep}"
             check(got, orc.per_head_forward(Xn, wl.weights_of(inp), w.d_head, w.causal, w.rope_base), w.dtype, f"replay {rep}")
+
+
+@pytest.mark.parametrize("shared", [False, True])
+def test_decode_replays_correctly_from_a_hip_graph(shared):
+    # a decode step is five kernel launches on the caller's stream (cache lengths travel by value), so a serving
+    # loop can capture it; every replay, with a fresh token and eager work in between, must equal the eager result
+    w = wl.scaled(wl.WORKLOADS["decode_32k_shared_kv" if shared else "decode_32k"], B=5, kv_len=700, d_model=256,
+                  n_heads=12, d_head=32, r1=3, r2=64, r3=64, rt1=2, rt2=32, rt3=64, recipe="fan_in", seed=63)
+    inp = wl.make_inputs(w)
+    inp["kv_len"] = np.array([700, 1, 129, 512, 333], dtype=np.int32)
+    lens = [int(v) for v in inp["kv_len"]]
+    rng = np.random.default_rng(78)
+    with Layer(w, inp, max_positions=701) as layer:
+        x = to_device(inp["X"][:, 0], w.dtype)
+        y = torch.empty_like(x)
+        K0 = to_device(inp["Lcache" if shared else "Kcache"], w.dtype)
+        V0 = None if shared else to_device(inp["Vcache"], w.dtype)
+        Kc, Vc = K0.clone(), (None if shared else V0.clone())
+        ws = layer.workspace(ta.tucker_attn_decode_workspace_bytes(layer.ctx, w.B))
+        ta.tucker_attn_decode(layer.ctx, layer.weights, x, y, Kc, Vc, lens, ws)           # first call outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                ta.tucker_attn_decode(layer.ctx, layer.weights, x, y, Kc, Vc, lens, ws)
+        torch.cuda.current_stream().wait_stream(side)
+        for rep in range(4):
+            xn = wl.round_to_storage(rng.standard_normal(inp["X"][:, 0].shape).astype(np.float32), w.dtype)
+            x.copy_(to_device(xn, w.dtype))
+            Kc.copy_(K0)
+            if not shared:
+                Vc.copy_(V0)
+            y.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            got, gotK = to_host(y), to_host(Kc)
+            Ke, Ve, ye = K0.clone(), (None if shared else V0.clone()), torch.empty_like(x)
+            ta.tucker_attn_decode(layer.ctx, layer.weights, x, ye, Ke, Ve, lens, ws)      # eager, same workspace
+            torch.cuda.synchronize()
+            assert np.array_equal(got, to_host(ye)) and np.array_equal(gotK, to_host(Ke)), f"replay {rep}"
+            if shared:
+                ref, _ = orc.decode_step_shared_kv(xn, inp["Lcache"], inp["kv_len"], wl.weights_of(inp), w.d_head,
+                                                   w.rope_base)
+            else:
+                ref, _, _ = orc.decode_step(xn, inp["Kcache"], inp["Vcache"], inp["kv_len"], wl.weights_of(inp),
+                                            w.d_head, w.rope_base)
+            check(got, ref, w.dtype, f"decode replay {rep}")
