@@ -181,7 +181,7 @@ int tucker_attn_decode(tucker_attn_ctx *ctx, const tucker_attn_weights *w,
  * (33 554 432 bytes) device array that is part of the loaded library (each GPU the library runs on
  * holds its own copy until the process ends).  The call allocates and frees nothing.
  *   - TUCKER_ATTN_WORKSPACE_TOO_SMALL if tucker_attn_decode_workspace_bytes(ctx, B) exceeds 32 MiB
- *     (the LLaMA-7B layer shape with ranks [8,128,128] needs about 15 MiB at any B); nothing is enqueued.
+ *     (the LLaMA-7B layer shape with ranks [8,128,128] needs at most 11.1 MiB, whatever B); nothing is enqueued.
  *   - Every call on a GPU, from any context, uses that GPU's one array: calls must be ordered on one
  *     stream or otherwise synchronised; calls that overlap on one GPU race.  The array keeps the last
  *     call's contents; no part of it has to start at zero (every piece is written before it is read
