@@ -207,15 +207,15 @@ BackwardWs carve_backward(const tucker_attn_ctx* c, void* ws, int B, int N) {
 // units, and never more splits than the longest cache has 64-key tiles.  The shared-latent variant of that kernel
 // rotates keys as it stages them and is bound by that arithmetic, not by HBM: it runs two rounds (52 us against 68
 // with one); the wave-private shared-latent kernel holds one workgroup per compute unit and takes 128 keys at a
-// time.  At most 64 splits: the merge kernel walks them one after the other (256 splits of one 128k-token
-// sequence: 34 us).
+// time.  At most 256 splits (a single sequence on 256 compute units): the merge spreads a sequence's splits over
+// thread groups, 16 at a time each.
 int decode_nsplit(const tucker_attn_ctx* c, int B, int longest) {
   const tucker_attn_config& f = c->cfg;
   const bool wave_private = decode_wave_private(f.dtype, f.r3, c->D, f.shared_kv);
   int n = (f.shared_kv && !wave_private ? 2 : 1) * c->n_cus / B;
   const int step = wave_private ? kDecodeRoundWave : kDecodeTile;  // keys a workgroup takes at a time
   const long tiles = ((long)longest + step - 1) / step;
-  if (n > 64) n = 64;
+  if (n > 256) n = 256;
   if (n > tiles) n = (int)tiles;
   return n < 1 ? 1 : n;
 }

@@ -720,6 +720,7 @@ __global__ __launch_bounds__(256) void decode_merge_heads_kernel(DecodeArgs p) {
   constexpr int CB = D / 32, CPT = D / 8;                         // channels per thread in the merge: 8 threads per row
   constexpr int RE = D + 16 / (int)sizeof(T);                     // padded LDS row
   __shared__ __attribute__((aligned(16))) T Ol[32 * RE];
+  __shared__ float px[256 * (CPT + 2)];                           // partial merges of the thread groups of a sequence
   const int head = blockIdx.x;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int h = lane / 32, lr = lane % 32;
@@ -735,8 +736,16 @@ __global__ __launch_bounds__(256) void decode_merge_heads_kernel(DecodeArgs p) {
   }
 
   // ---- merged, normalised O_i[tok][c] -> LDS (c stored in acc order inside each 32-block) ----
+  // Eight threads share a sequence's D channels.  With fewer than 32 sequences the 32 thread rows are dealt out as
+  // S = 32 / Bp groups per sequence (Bp = batch rounded up to a power of two): group sg merges the splits sg, sg + S,
+  // ..., and the S partial merges of a sequence are combined through LDS in group order, so that one long sequence
+  // with many splits is not merged by eight threads alone.  The result does not depend on timing.
   {
-    const int tok = threadIdx.x / 8, c0 = (threadIdx.x % 8) * CPT;
+    int Bp = 1;
+    while (Bp < p.Bsz) Bp *= 2;                                   // 1 .. 32
+    const int S = 32 / Bp;
+    const int row = threadIdx.x / 8, cg = threadIdx.x % 8, c0 = cg * CPT;
+    const int tok = row % Bp, sg = row / Bp;
     float num[CPT];
 #pragma unroll
     for (int e = 0; e < CPT; ++e) num[e] = 0.f;
@@ -744,12 +753,12 @@ __global__ __launch_bounds__(256) void decode_merge_heads_kernel(DecodeArgs p) {
     if (tok < p.Bsz) {
       constexpr int U = 16;                                       // splits whose loads are issued together (one
                                                                   // workgroup per compute unit: registers are plentiful)
-      for (int s0 = 0; s0 < p.nsplit; s0 += U) {
+      for (int s0 = sg; s0 < p.nsplit; s0 += U * S) {
         float mv[U], lv[U];
         f32x4 ov[U][CPT / 4];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          const long ps = ((long)tok * p.nsplit + min(s0 + u, p.nsplit - 1)) * HB32 + head;
+          const long ps = ((long)tok * p.nsplit + min(s0 + u * S, p.nsplit - 1)) * HB32 + head;
           mv[u] = p.part_m[ps];
           lv[u] = p.part_l[ps];
 #pragma unroll
@@ -758,7 +767,7 @@ __global__ __launch_bounds__(256) void decode_merge_heads_kernel(DecodeArgs p) {
         float mb = mrun;
 #pragma unroll
         for (int u = 0; u < U; ++u)
-          if (s0 + u < p.nsplit) mb = fmaxf(mb, mv[u]);
+          if (s0 + u * S < p.nsplit) mb = fmaxf(mb, mv[u]);
         if (mb == -INFINITY) continue;                            // only empty splits so far
         const float a = fast_exp2(mrun - mb);                     // 0 while mrun is still -inf
         den *= a;
@@ -767,7 +776,7 @@ __global__ __launch_bounds__(256) void decode_merge_heads_kernel(DecodeArgs p) {
         mrun = mb;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          const bool live = s0 + u < p.nsplit && mv[u] != -INFINITY;
+          const bool live = s0 + u * S < p.nsplit && mv[u] != -INFINITY;
           const float w = live ? fast_exp2(mv[u] - mb) : 0.f;
           den += w * lv[u];
 #pragma unroll
@@ -777,11 +786,33 @@ __global__ __launch_bounds__(256) void decode_merge_heads_kernel(DecodeArgs p) {
         }
       }
     }
-    const float inv = tok < p.Bsz ? 1.f / den : 0.f;              // rows past the batch are zero
+    if (S > 1) {                                                  // (the same for the whole workgroup)
+      float* mine = px + (row * 8 + cg) * (CPT + 2);
+#pragma unroll
+      for (int e = 0; e < CPT; ++e) mine[e] = num[e];
+      mine[CPT] = mrun;
+      mine[CPT + 1] = den;
+      __syncthreads();
+      if (sg == 0 && tok < p.Bsz) {
+        for (int j = 1; j < S; ++j) {                             // group 0 holds its own part already
+          const float* other = px + ((tok + j * Bp) * 8 + cg) * (CPT + 2);
+          const float mo_ = other[CPT];
+          if (mo_ == -INFINITY) continue;
+          const float mb = fmaxf(mrun, mo_);
+          const float a = fast_exp2(mrun - mb), b = fast_exp2(mo_ - mb);
+          den = den * a + other[CPT + 1] * b;
+#pragma unroll
+          for (int e = 0; e < CPT; ++e) num[e] = num[e] * a + other[e] * b;
+          mrun = mb;
+        }
+      }
+    }
+    // thread row `row` writes LDS row `row`: a sequence's merged output from its group 0, zeros elsewhere
+    const float inv = (sg == 0 && tok < p.Bsz) ? 1.f / den : 0.f;
 #pragma unroll
     for (int q = 0; q < CPT / 4; ++q) {
       const int c = c0 + 4 * q;                                   // four consecutive channels keep their order
-      store4(Ol + tok * RE + (c & ~31) + acc_pos(c & 31), num[4 * q] * inv, num[4 * q + 1] * inv, num[4 * q + 2] * inv,
+      store4(Ol + row * RE + (c & ~31) + acc_pos(c & 31), num[4 * q] * inv, num[4 * q + 1] * inv, num[4 * q + 2] * inv,
              num[4 * q + 3] * inv);
     }
   }
