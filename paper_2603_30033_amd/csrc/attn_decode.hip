@@ -794,16 +794,19 @@ __global__ __launch_bounds__(256) void decode_merge_heads_kernel(DecodeArgs p) {
       mine[CPT + 1] = den;
       __syncthreads();
       if (sg == 0 && tok < p.Bsz) {
-        for (int j = 1; j < S; ++j) {                             // group 0 holds its own part already
-          const float* other = px + ((tok + j * Bp) * 8 + cg) * (CPT + 2);
-          const float mo_ = other[CPT];
-          if (mo_ == -INFINITY) continue;
-          const float mb = fmaxf(mrun, mo_);
-          const float a = fast_exp2(mrun - mb), b = fast_exp2(mo_ - mb);
-          den = den * a + other[CPT + 1] * b;
+        // reference = the largest of the groups' references; then the parts are scaled and added in group order
+        float mall = mrun;
+        for (int j = 1; j < S; ++j) mall = fmaxf(mall, px[((tok + j * Bp) * 8 + cg) * (CPT + 2) + CPT]);
+        const float a0 = mrun == -INFINITY ? 0.f : fast_exp2(mrun - mall);   // (mall is finite: some split is not empty)
+        den *= a0;
 #pragma unroll
-          for (int e = 0; e < CPT; ++e) num[e] = num[e] * a + other[e] * b;
-          mrun = mb;
+        for (int e = 0; e < CPT; ++e) num[e] *= a0;
+        for (int j = 1; j < S; ++j) {
+          const float* other = px + ((tok + j * Bp) * 8 + cg) * (CPT + 2);
+          const float b = other[CPT] == -INFINITY ? 0.f : fast_exp2(other[CPT] - mall);
+          den += other[CPT + 1] * b;
+#pragma unroll
+          for (int e = 0; e < CPT; ++e) num[e] += other[e] * b;
         }
       }
     }
