@@ -736,21 +736,23 @@ __global__ __launch_bounds__(256) void decode_merge_heads_kernel(DecodeArgs p) {
   }
 
   // ---- merged, normalised O_i[tok][c] -> LDS (c stored in acc order inside each 32-block) ----
-  // Eight threads share a sequence's D channels.  With fewer than 32 sequences the 32 thread rows are dealt out as
-  // S = 32 / Bp groups per sequence (Bp = batch rounded up to a power of two): group sg merges the splits sg, sg + S,
-  // ..., and the S partial merges of a sequence are combined through LDS in group order, so that one long sequence
-  // with many splits is not merged by eight threads alone.  The result does not depend on timing.
+  // Eight threads share a sequence's D channels.  A sequence with more than 16 splits (few sequences, long caches)
+  // gets S groups of such threads out of the 32 thread rows, as many as keep a group's share at 16 splits if the
+  // batch leaves that many rows free: group sg merges the splits sg, sg + S, ..., and the S partial merges of a
+  // sequence are combined through LDS in group order.  With 16 splits or fewer (S = 1) there is no exchange.  The
+  // result does not depend on timing.
   {
     int Bp = 1;
-    while (Bp < p.Bsz) Bp *= 2;                                   // 1 .. 32
-    const int S = 32 / Bp;
+    while (Bp < p.Bsz) Bp *= 2;                                   // batch rounded up to a power of two, 1 .. 32
+    int S = 1;
+    while (S * 16 < p.nsplit && 2 * S * Bp <= 32) S *= 2;
     const int row = threadIdx.x / 8, cg = threadIdx.x % 8, c0 = cg * CPT;
     const int tok = row % Bp, sg = row / Bp;
     float num[CPT];
 #pragma unroll
     for (int e = 0; e < CPT; ++e) num[e] = 0.f;
     float mrun = -INFINITY, den = 0.f;
-    if (tok < p.Bsz) {
+    if (tok < p.Bsz && sg < S) {
       constexpr int U = 16;                                       // splits whose loads are issued together (one
                                                                   // workgroup per compute unit: registers are plentiful)
       for (int s0 = sg; s0 < p.nsplit; s0 += U * S) {
